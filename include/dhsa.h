@@ -1,0 +1,157 @@
+/*
+ * libdhsa -- the prefill hot path of Dynamic Hierarchical Sparse Attention
+ * (arXiv 2510.24606) for AMD MI355X (gfx950).  C ABI: plain pointers and sizes.
+ *
+ * One attention layer, batch 1 (a batch is a caller-side loop, as in the
+ * paper's Sec. 4 "batch handling").  Per query head h (GQA: kv-head g = h / G,
+ * G = H_q / H_kv) the path is
+ *   1. pool Q and K over the variable-length chunks given by the boundaries B
+ *      (Sec. 3.3, Eq. 4: x_C = sqrt(len)/len * sum of the chunk's vectors);
+ *   2. chunk similarity S_c = Q_c K_c^T, unscaled (Sec. 3.3);
+ *   3. rank the key chunks of every query chunk by S_c, larger first, equal
+ *      scores by lower chunk id (Sec. 3.1 Step 2; Alg. 1 "Argsort");
+ *   4. per query ROW i take tokens in ranked order, clipped to keys j <= i,
+ *      until exactly min(N_b, i+1) are taken; the last chunk taken keeps its
+ *      lowest indices (Alg. 1 walk/append/truncate with q_max = i + 1);
+ *   5. softmax(q_i . k_j * scale) over the selected keys only, times V
+ *      (Alg. 2 / Alg. 3; App. C "Backend implementations").
+ * Steps 1-4 are dhsa_route (result: a compact routing plan), step 5 is
+ * dhsa_sparse_prefill, dhsa_prefill runs both on one stream.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers host addresses.
+ *   - Q is [H_q, L, D], K and V are [H_kv, L, D], O is [H_q, L, D]; D contiguous;
+ *     element strides between heads and rows are in the problem struct (0 means
+ *     packed).  Row starts must be 16-byte aligned.
+ *   - B is a HOST array of N_c+1 int32 with B[0] = 0 < B[1] < ... < B[N_c] = L;
+ *     chunk k holds tokens [B[k], B[k+1]).  It is validated on the host before
+ *     any device work and copied into the plan.
+ *   - The caller owns every buffer (plan and workspace included, sized by the
+ *     *_bytes calls, 256-byte aligned).  The library allocates nothing, keeps
+ *     no state between calls, and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     results are valid once the caller has synchronised that stream.
+ *   - Every entry point returns a dhsa_status; arguments are validated before
+ *     the first device call and on error nothing is written or launched.
+ *   - Inputs must be finite; N_b > L behaves as N_b = L.
+ *   - Limits: D in {64, 128}; 1 <= N_c <= 8192; L < 2^31.
+ *   - Routing arithmetic (pooling, S_c, ranking) is fp64 so that the chosen
+ *     index sets do not depend on summation order beyond ~1e-13 score gaps.
+ *     Attention: DHSA_BF16 uses bf16 MFMA with fp32 softmax and accumulators
+ *     (probabilities are rounded to bf16 before the PV product); DHSA_F32 uses
+ *     fp32 arithmetic throughout.  O has the input dtype.
+ */
+#ifndef DHSA_H
+#define DHSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DHSA_OK = 0,
+    DHSA_ERR_NULL = 1,        /* a required pointer is NULL                               */
+    DHSA_ERR_SHAPE = 2,       /* L, H_q, H_kv, D, N_c or a stride out of the stated range */
+    DHSA_ERR_BOUNDARIES = 3,  /* B not strictly increasing from 0 to L                    */
+    DHSA_ERR_BUDGET = 4,      /* N_b < 1                                                  */
+    DHSA_ERR_DTYPE = 5,       /* dtype not DHSA_F32 / DHSA_BF16                           */
+    DHSA_ERR_WORKSPACE = 6,   /* plan or workspace smaller than *_bytes() says            */
+    DHSA_ERR_HIP = 7,         /* a HIP runtime call or launch failed                      */
+    DHSA_ERR_PLAN = 8,        /* the plan does not belong to this problem                 */
+    DHSA_ERR_ALIGN = 9        /* a pointer or stride breaks the 16-byte row alignment     */
+} dhsa_status;
+
+typedef enum { DHSA_F32 = 0, DHSA_BF16 = 1 } dhsa_dtype;
+
+/* Problem statement of Sec. 3.1 / Alg. 1-3: sequence length L, chunk count N_c
+ * (boundaries passed separately), per-row token budget N_b, GQA head counts. */
+typedef struct {
+    int64_t L;
+    int32_t H_q, H_kv, D;
+    int32_t N_c;
+    int32_t N_b;
+    int32_t dtype;            /* dhsa_dtype of Q, K, V and O                       */
+    float scale;              /* softmax scale of step 5; 0 means 1/sqrt(D)        */
+    int64_t q_stride_h, q_stride_l;   /* in elements; 0 = packed [H, L, D]         */
+    int64_t k_stride_h, k_stride_l;
+    int64_t v_stride_h, v_stride_l;
+    int64_t o_stride_h, o_stride_l;
+} dhsa_problem;
+
+/*
+ * Layout of the routing plan (device memory, int32 words, little endian).  It
+ * is the sparsity mask M of Sec. 3.1 in compact form: all rows of query chunk l
+ * share one ranking and differ only in v = i + 1 - B[l], the visible part of
+ * their own chunk.
+ *   words [0, 16)            header: magic 'DHSA', version, H_q, N_c, N_b (clamped to L),
+ *                            stride, L, T1 (row tiles per head), off_B, off_count,
+ *                            off_entries, off_tiles (word offsets), rest 0
+ *   off_B      int32[N_c+1]  the boundaries
+ *   off_count  int32[H_q][N_c]          number of entries of (h, l)
+ *   off_entries int32[H_q][N_c][stride][2]   entries, ascending chunk id:
+ *        word 0: key chunk id k | (pos << 28), pos = 0 ranked before chunk l,
+ *                1 = chunk l itself, 2 ranked after chunk l
+ *        word 1: rem = N_b - (tokens of other chunks taken before chunk k)
+ *      Row i of chunk l takes from entry (k, pos, rem) the tokens B[k] + t with
+ *        t < min(len_k, rem)            if pos = 0
+ *        t < min(v, rem)                if pos = 1
+ *        t < min(len_k, rem - v)        if pos = 2
+ *      Only chunks some row of l takes a token from are listed.
+ *   off_tiles  int32[T1][2]  row tiles of one head: (chunk l, first row), rows
+ *                            [row, min(row + 128, B[l+1])), ordered by row
+ */
+#define DHSA_PLAN_MAGIC 0x41534844
+#define DHSA_PLAN_VERSION 1
+#define DHSA_ROW_TILE 128
+
+/* Device bytes the plan / the routing workspace need.  0 on invalid arguments. */
+size_t dhsa_plan_bytes(const dhsa_problem *prob, const int32_t *B_host);
+size_t dhsa_workspace_bytes(const dhsa_problem *prob, const int32_t *B_host);
+
+/* Steps 1-4 (Sec. 3.1, 3.3; Alg. 1): Q_dev, K_dev -> plan_dev.  ws_dev is
+ * scratch (pooled vectors and S_c); its contents after the call are readable
+ * through the dhsa_debug_* hooks until the next call that uses it. */
+dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
+                       const int32_t *B_host, void *plan_dev, size_t plan_bytes, void *ws_dev,
+                       size_t ws_bytes, void *stream);
+
+/* Step 5 (Alg. 2 / Alg. 3): exact softmax attention over the keys the plan
+ * selects, O_dev[h, i, :] for every row.  The plan must come from dhsa_route on
+ * the same problem and boundaries (it may be reused across calls, as the paper
+ * caches routing results). */
+dhsa_status dhsa_sparse_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
+                                const void *V_dev, const int32_t *B_host, const void *plan_dev,
+                                size_t plan_bytes, void *O_dev, void *stream);
+
+/* Steps 1-5 on one stream (Sec. 3.4 "Workflow"). */
+dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev,
+                         const int32_t *B_host, void *O_dev, void *plan_dev, size_t plan_bytes,
+                         void *ws_dev, size_t ws_bytes, void *stream);
+
+/* ---- inspection hooks (tests, stage-wise parity) ---- */
+
+/* Expand the plan into explicit index sets I_{h,i} (Alg. 1's output) for one
+ * head and a HOST list of rows: idx_dev[n_rows][cap] ascending, padded with -1,
+ * cnt_dev[n_rows]; cap >= min(N_b, L).  rows are copied to rows_dev_scratch
+ * (device, n_rows int64) by the call. */
+dhsa_status dhsa_plan_expand_rows(const dhsa_problem *prob, const void *plan_dev, size_t plan_bytes,
+                                  int32_t head, const int64_t *rows_host, int32_t n_rows,
+                                  int64_t *rows_dev_scratch, int32_t *idx_dev, int32_t cap,
+                                  int32_t *cnt_dev, void *stream);
+
+/* Copy the pooled vectors (fp64, Qc_dev [H_q][N_c][D], Kc_dev [H_kv][N_c][D])
+ * and/or the lower triangle of S_c (fp64, Sc_dev [H_q][N_c][N_c], entries with
+ * k > l are not written) out of a workspace dhsa_route has filled.  NULL skips. */
+dhsa_status dhsa_debug_routing(const dhsa_problem *prob, const int32_t *B_host, const void *ws_dev,
+                               size_t ws_bytes, double *Qc_dev, double *Kc_dev, double *Sc_dev, void *stream);
+
+const char *dhsa_status_string(dhsa_status s);
+int dhsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DHSA_H */

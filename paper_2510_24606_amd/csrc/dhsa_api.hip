@@ -1,0 +1,273 @@
+// Host side of libdhsa: argument validation, plan/workspace layout, launches.
+// See include/dhsa.h for the contract of every entry point.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "dhsa_internal.h"
+
+using namespace dhsa;
+
+namespace {
+
+int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Validate the problem and the boundaries (host only, no device call).
+dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
+    if (!in || !B) return DHSA_ERR_NULL;
+    if (in->dtype != DHSA_F32 && in->dtype != DHSA_BF16) return DHSA_ERR_DTYPE;
+    if (in->L < 1 || in->L >= (int64_t)1 << 31) return DHSA_ERR_SHAPE;
+    if (in->H_q < 1 || in->H_kv < 1 || in->H_q % in->H_kv != 0 || in->H_q > 65535 - in->H_kv) return DHSA_ERR_SHAPE;
+    if (in->D != 64 && in->D != 128) return DHSA_ERR_SHAPE;
+    if (in->N_c < 1 || in->N_c > kMaxChunks || in->N_c > in->L) return DHSA_ERR_SHAPE;
+    if (in->N_b < 1) return DHSA_ERR_BUDGET;
+    if (!(in->scale >= 0.f) || !isfinite(in->scale)) return DHSA_ERR_SHAPE;
+    if (B[0] != 0 || (int64_t)B[in->N_c] != in->L) return DHSA_ERR_BOUNDARIES;
+    for (int k = 0; k < in->N_c; ++k)
+        if (B[k + 1] <= B[k]) return DHSA_ERR_BOUNDARIES;
+    p->L = in->L; p->H_q = in->H_q; p->H_kv = in->H_kv; p->G = in->H_q / in->H_kv; p->D = in->D;
+    p->N_c = in->N_c;
+    p->N_b = (int)std::min<int64_t>(in->N_b, in->L);
+    p->dtype = in->dtype;
+    p->scale = in->scale > 0.f ? in->scale : 1.0f / sqrtf((float)in->D);
+    const int64_t row = in->D, head = in->L * in->D;
+    const int esz = in->dtype == DHSA_F32 ? 4 : 2;
+    struct { int64_t in_h, in_l, *out_h, *out_l; } st[4] = {
+        {in->q_stride_h, in->q_stride_l, &p->qs_h, &p->qs_l}, {in->k_stride_h, in->k_stride_l, &p->ks_h, &p->ks_l},
+        {in->v_stride_h, in->v_stride_l, &p->vs_h, &p->vs_l}, {in->o_stride_h, in->o_stride_l, &p->os_h, &p->os_l}};
+    for (auto &s : st) {
+        *s.out_l = s.in_l ? s.in_l : row;
+        *s.out_h = s.in_h ? s.in_h : head;
+        if (*s.out_l < row || *s.out_h < 0) return DHSA_ERR_SHAPE;
+        if ((*s.out_l * esz) % 16 != 0 || (*s.out_h * esz) % 16 != 0) return DHSA_ERR_ALIGN;
+    }
+    return DHSA_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+PlanLayout plan_layout(const Prob &p, const int32_t *B) {
+    PlanLayout pl;
+    // most chunks any query chunk can list: the chunks taken before the budget
+    // is met number at most 1 + (how many of the shortest chunks sum to < N_b),
+    // plus the query chunk itself
+    std::vector<int32_t> lens(p.N_c);
+    int T1 = 0;
+    for (int k = 0; k < p.N_c; ++k) {
+        lens[k] = B[k + 1] - B[k];
+        T1 += (lens[k] + kRowTile - 1) / kRowTile;
+    }
+    std::sort(lens.begin(), lens.end());
+    int64_t acc = 0;
+    int n = 0;
+    while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
+    pl.stride = std::min(p.N_c, n + 2);
+    pl.T1 = T1;
+    pl.off_B = 16;
+    pl.off_count = align_up(pl.off_B + p.N_c + 1, 4);
+    pl.off_entries = align_up(pl.off_count + (int64_t)p.H_q * p.N_c, 4);
+    pl.off_tiles = align_up(pl.off_entries + (int64_t)p.H_q * p.N_c * pl.stride * 2, 4);
+    pl.words = align_up(pl.off_tiles + (int64_t)T1 * 2, 64);
+    return pl;
+}
+
+WsLayout ws_layout(const Prob &p) {
+    WsLayout w;
+    w.off_Qc = 0;
+    w.off_Kc = align_up(w.off_Qc + (int64_t)p.H_q * p.N_c * p.D, 32);
+    w.off_Sc = align_up(w.off_Kc + (int64_t)p.H_kv * p.N_c * p.D, 32);
+    w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_c * p.N_c, 32);
+    return w;
+}
+
+PlanView plan_view(const PlanLayout &pl, const void *plan) {
+    const int32_t *w = static_cast<const int32_t *>(plan);
+    PlanView v;
+    v.B = w + pl.off_B;
+    v.count = w + pl.off_count;
+    v.entries = w + pl.off_entries;
+    v.tiles = w + pl.off_tiles;
+    v.stride = pl.stride;
+    v.T1 = pl.T1;
+    return v;
+}
+
+dhsa_status hip_status(hipError_t e) { return e == hipSuccess ? DHSA_OK : DHSA_ERR_HIP; }
+
+dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, const void *Q, const void *K,
+                       const int32_t *B_host, void *plan, void *ws, hipStream_t s) {
+    int32_t *pw = static_cast<int32_t *>(plan);
+    double *wd = static_cast<double *>(ws);
+    hipError_t e = hipMemcpyAsync(pw + pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
+                                  hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return DHSA_ERR_HIP;
+    if ((e = launch_setup(p, pl, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
+    if ((e = launch_pool(p, Q, K, pw + pl.off_B, wd + wl.off_Qc, wd + wl.off_Kc, s)) != hipSuccess)
+        return DHSA_ERR_HIP;
+    if ((e = launch_scores(p, wd + wl.off_Qc, wd + wl.off_Kc, wd + wl.off_Sc, s)) != hipSuccess)
+        return DHSA_ERR_HIP;
+    if ((e = launch_select(p, pl, wd + wl.off_Sc, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
+    return DHSA_OK;
+}
+
+dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, const void *K, const void *V,
+                        const void *plan, void *O, hipStream_t s) {
+    const PlanView pv = plan_view(pl, plan);
+    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
+                                          : launch_attn_rowwise(p, pv, Q, K, V, O, s);
+    return hip_status(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+__attribute__((visibility("default"))) size_t dhsa_plan_bytes(const dhsa_problem *prob, const int32_t *B_host) {
+    Prob p;
+    if (resolve(prob, B_host, &p) != DHSA_OK) return 0;
+    return (size_t)plan_layout(p, B_host).words * sizeof(int32_t);
+}
+
+__attribute__((visibility("default"))) size_t dhsa_workspace_bytes(const dhsa_problem *prob,
+                                                                   const int32_t *B_host) {
+    Prob p;
+    if (resolve(prob, B_host, &p) != DHSA_OK) return 0;
+    return (size_t)ws_layout(p).doubles * sizeof(double);
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev,
+                                                              const void *K_dev, const int32_t *B_host,
+                                                              void *plan_dev, size_t plan_bytes, void *ws_dev,
+                                                              size_t ws_bytes, void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !plan_dev || !ws_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(plan_dev) || misaligned(ws_dev)) return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    const WsLayout wl = ws_layout(p);
+    if (plan_bytes < (size_t)pl.words * 4 || ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
+    return route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, static_cast<hipStream_t>(stream));
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_sparse_prefill(const dhsa_problem *prob, const void *Q_dev,
+                                                                       const void *K_dev, const void *V_dev,
+                                                                       const int32_t *B_host, const void *plan_dev,
+                                                                       size_t plan_bytes, void *O_dev,
+                                                                       void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) || misaligned(O_dev))
+        return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
+    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, static_cast<hipStream_t>(stream));
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev,
+                                                                const void *K_dev, const void *V_dev,
+                                                                const int32_t *B_host, void *O_dev, void *plan_dev,
+                                                                size_t plan_bytes, void *ws_dev, size_t ws_bytes,
+                                                                void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev || !ws_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) ||
+        misaligned(O_dev) || misaligned(ws_dev))
+        return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    const WsLayout wl = ws_layout(p);
+    if (plan_bytes < (size_t)pl.words * 4 || ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, s);
+    if (st != DHSA_OK) return st;
+    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
+    const dhsa_problem *prob, const void *plan_dev, size_t plan_bytes, int32_t head, const int64_t *rows_host,
+    int32_t n_rows, int64_t *rows_dev_scratch, int32_t *idx_dev, int32_t cap, int32_t *cnt_dev, void *stream) {
+    if (!prob || !plan_dev || !rows_host || !rows_dev_scratch || !idx_dev || !cnt_dev) return DHSA_ERR_NULL;
+    // the boundaries live in the plan; only the scalar fields of the problem are checked here
+    if (prob->L < 1 || prob->N_c < 1 || prob->N_c > kMaxChunks || prob->H_q < 1 || prob->N_b < 1)
+        return DHSA_ERR_SHAPE;
+    if (head < 0 || head >= prob->H_q || n_rows < 0) return DHSA_ERR_SHAPE;
+    const int nb = (int)std::min<int64_t>(prob->N_b, prob->L);
+    if (cap < nb) return DHSA_ERR_WORKSPACE;
+    for (int t = 0; t < n_rows; ++t)
+        if (rows_host[t] < 0 || rows_host[t] >= prob->L) return DHSA_ERR_SHAPE;
+    if (plan_bytes < 64) return DHSA_ERR_PLAN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // read the header back: the layout offsets are part of the plan
+    int32_t hdr[16];
+    if (hipMemcpyAsync(hdr, plan_dev, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return DHSA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return DHSA_ERR_HIP;
+    if (hdr[0] != DHSA_PLAN_MAGIC || hdr[1] != DHSA_PLAN_VERSION || hdr[2] != prob->H_q || hdr[3] != prob->N_c ||
+        hdr[4] != nb || (int64_t)hdr[6] != prob->L)
+        return DHSA_ERR_PLAN;
+    PlanLayout pl;
+    pl.stride = hdr[5]; pl.T1 = hdr[7];
+    pl.off_B = hdr[8]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
+    pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
+    if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
+    Prob p;
+    memset(&p, 0, sizeof(p));
+    p.L = prob->L; p.H_q = prob->H_q; p.N_c = prob->N_c; p.N_b = nb;
+    if (n_rows == 0) return DHSA_OK;
+    if (hipMemcpyAsync(rows_dev_scratch, rows_host, sizeof(int64_t) * (size_t)n_rows, hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+        return DHSA_ERR_HIP;
+    return hip_status(launch_expand(p, plan_view(pl, plan_dev), head, rows_dev_scratch, n_rows, idx_dev, cap,
+                                    cnt_dev, s));
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_debug_routing(const dhsa_problem *prob,
+                                                                      const int32_t *B_host, const void *ws_dev,
+                                                                      size_t ws_bytes, double *Qc_dev,
+                                                                      double *Kc_dev, double *Sc_dev,
+                                                                      void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!ws_dev) return DHSA_ERR_NULL;
+    const WsLayout wl = ws_layout(p);
+    if (ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const double *wd = static_cast<const double *>(ws_dev);
+    hipError_t e = hipSuccess;
+    if (Qc_dev)
+        e = hipMemcpyAsync(Qc_dev, wd + wl.off_Qc, sizeof(double) * (size_t)p.H_q * p.N_c * p.D,
+                           hipMemcpyDeviceToDevice, s);
+    if (e == hipSuccess && Kc_dev)
+        e = hipMemcpyAsync(Kc_dev, wd + wl.off_Kc, sizeof(double) * (size_t)p.H_kv * p.N_c * p.D,
+                           hipMemcpyDeviceToDevice, s);
+    if (e == hipSuccess && Sc_dev)
+        e = hipMemcpyAsync(Sc_dev, wd + wl.off_Sc, sizeof(double) * (size_t)p.H_q * p.N_c * p.N_c,
+                           hipMemcpyDeviceToDevice, s);
+    return hip_status(e);
+}
+
+__attribute__((visibility("default"))) const char *dhsa_status_string(dhsa_status s) {
+    switch (s) {
+        case DHSA_OK: return "ok";
+        case DHSA_ERR_NULL: return "null pointer";
+        case DHSA_ERR_SHAPE: return "shape out of range";
+        case DHSA_ERR_BOUNDARIES: return "boundaries not strictly increasing from 0 to L";
+        case DHSA_ERR_BUDGET: return "token budget below 1";
+        case DHSA_ERR_DTYPE: return "unsupported dtype";
+        case DHSA_ERR_WORKSPACE: return "plan or workspace too small";
+        case DHSA_ERR_HIP: return "HIP runtime error";
+        case DHSA_ERR_PLAN: return "plan does not match the problem";
+        case DHSA_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+    }
+    return "unknown status";
+}
+
+__attribute__((visibility("default"))) int dhsa_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Internal declarations shared by the HIP translation units of libdhsa.
+// Nothing here is part of the C ABI (see include/dhsa.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dhsa.h"
+
+namespace dhsa {
+
+constexpr int kRowTile = DHSA_ROW_TILE;  // query rows per attention workgroup
+constexpr int kMaxChunks = 8192;         // N_c limit (LDS ranking of one query chunk)
+constexpr int kPosShift = 28;            // plan entry word 0 = chunk id | pos << 28
+constexpr int kChunkMask = (1 << kPosShift) - 1;
+
+// Resolved problem: strides filled in, budget clamped, scale chosen.
+struct Prob {
+    int64_t L;
+    int H_q, H_kv, G, D, N_c, N_b;  // N_b already clamped to L
+    int dtype;
+    float scale;
+    int64_t qs_h, qs_l, ks_h, ks_l, vs_h, vs_l, os_h, os_l;
+};
+
+// Word offsets inside the plan buffer (see the layout comment in dhsa.h).
+struct PlanLayout {
+    int stride;       // entries per (h, l)
+    int T1;           // row tiles per head
+    int64_t off_B, off_count, off_entries, off_tiles, words;
+};
+
+// Device-side view of a plan.
+struct PlanView {
+    const int32_t *B;        // [N_c + 1]
+    const int32_t *count;    // [H_q][N_c]
+    const int32_t *entries;  // [H_q][N_c][stride][2]
+    const int32_t *tiles;    // [T1][2]
+    int stride, T1;
+};
+
+// Workspace layout in doubles.
+struct WsLayout {
+    int64_t off_Qc, off_Kc, off_Sc, doubles;
+};
+
+// ---- launchers (each enqueues on `s` and returns the launch status) ----
+hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
+hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, double *Qc,
+                       double *Kc, hipStream_t s);
+hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, double *Sc, hipStream_t s);
+hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s);
+hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
+                         int32_t *idx, int cap, int32_t *cnt, hipStream_t s);
+hipError_t launch_attn_rowwise(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
+                               void *O, hipStream_t s);
+hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
+                            void *O, hipStream_t s);
+
+// ---- small device helpers ----
+__device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N_c, int64_t i) {
+    int lo = 0, hi = N_c;  // B[lo] <= i < B[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if ((int64_t)B[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Tokens row (visible own-chunk count v) takes from a plan entry.
+__device__ __forceinline__ int entry_take(int pos, int rem, int len_k, int v) {
+    int lim = (pos == 1) ? v : len_k;
+    int room = (pos == 2) ? rem - v : rem;
+    int t = room < lim ? room : lim;
+    return t > 0 ? t : 0;
+}
+
+// Exclusive prefix sum of one int per thread over a 256-thread block (wave
+// shuffles + one LDS slot per wave).  `total` receives the block sum.  Contains
+// two block barriers; s_wave is an int[4] in LDS.
+__device__ __forceinline__ int block_excl_scan(int val, int *s_wave, int *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = val;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+    }
+    __syncthreads();  // protects s_wave from its previous use
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        int x = s_wave[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    *total = tot;
+    return base + inc - val;
+}
+
+}  // namespace dhsa

@@ -1,0 +1,398 @@
+// Routing kernels of libdhsa: plan set-up, chunk pooling (Sec. 3.3 Eq. 4),
+// chunk similarity S_c = Q_c K_c^T (Sec. 3.3), ranking and per-row budget
+// (Sec. 3.1 Step 2, Alg. 1), and the plan -> index-set expansion hook.
+//
+// All routing arithmetic is fp64: pooled sums of bf16 inputs are then exact
+// (order-free), and S_c carries ~1e-14 absolute error, so the ranking does not
+// hinge on summation order.
+#include "dhsa_internal.h"
+
+namespace dhsa {
+
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// Plan header + row-tile table.  One block; B is already in the plan.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int N_c,
+                                               int N_b, int64_t L) {
+    __shared__ int s_part[256];
+    __shared__ int s_carry;
+    const int tid = threadIdx.x;
+    const int32_t *B = plan + pl.off_B;
+    int32_t *tiles = plan + pl.off_tiles;
+    if (tid < 16) {
+        int32_t w = 0;
+        switch (tid) {
+            case 0: w = DHSA_PLAN_MAGIC; break;
+            case 1: w = DHSA_PLAN_VERSION; break;
+            case 2: w = H_q; break;
+            case 3: w = N_c; break;
+            case 4: w = N_b; break;
+            case 5: w = pl.stride; break;
+            case 6: w = (int32_t)L; break;
+            case 7: w = pl.T1; break;
+            case 8: w = (int32_t)pl.off_B; break;
+            case 9: w = (int32_t)pl.off_count; break;
+            case 10: w = (int32_t)pl.off_entries; break;
+            case 11: w = (int32_t)pl.off_tiles; break;
+            default: break;
+        }
+        plan[tid] = w;
+    }
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int base = 0; base < N_c; base += 256) {
+        int l = base + tid;
+        int b0 = 0, len = 0, nsub = 0;
+        if (l < N_c) {
+            b0 = B[l];
+            len = B[l + 1] - b0;
+            nsub = (len + kRowTile - 1) / kRowTile;
+        }
+        s_part[tid] = nsub;
+        __syncthreads();
+        // Hillis-Steele inclusive scan over the 256 slab entries
+        for (int off = 1; off < 256; off <<= 1) {
+            int v = (tid >= off) ? s_part[tid - off] : 0;
+            __syncthreads();
+            s_part[tid] += v;
+            __syncthreads();
+        }
+        int start = s_carry + s_part[tid] - nsub;
+        for (int s = 0; s < nsub; ++s) {
+            tiles[2 * (start + s)] = l;
+            tiles[2 * (start + s) + 1] = b0 + s * kRowTile;
+        }
+        __syncthreads();
+        if (tid == 255) s_carry += s_part[255];
+        __syncthreads();
+    }
+}
+
+hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s) {
+    hipLaunchKernelGGL(k_setup, dim3(1), dim3(256), 0, s, plan, pl, p.H_q, p.N_c, p.N_b, p.L);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Chunk pooling, Eq. 4: X_c[h, k, :] = (sqrt(len)/len) * sum_{i in chunk k} X[h, i, :].
+// One block per (chunk, head); a row of D elements is read by D*sizeof(T)/16
+// threads with 16-byte loads, row groups are summed through LDS.  HBM-bound.
+// ---------------------------------------------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPer16 = 4;
+    __device__ static void unpack(const uint4 &u, double *acc) {
+        acc[0] += (double)__uint_as_float(u.x);
+        acc[1] += (double)__uint_as_float(u.y);
+        acc[2] += (double)__uint_as_float(u.z);
+        acc[3] += (double)__uint_as_float(u.w);
+    }
+};
+struct bf16_t { uint16_t bits; };
+template <> struct Elem<bf16_t> {
+    static constexpr int kPer16 = 8;
+    __device__ static void unpack(const uint4 &u, double *acc) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += (double)__uint_as_float(w[i] << 16);
+            acc[2 * i + 1] += (double)__uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *__restrict__ K,
+                                              const int32_t *__restrict__ B, double *__restrict__ Qc,
+                                              double *__restrict__ Kc, int H_q, int N_c, int64_t qs_h,
+                                              int64_t qs_l, int64_t ks_h, int64_t ks_l) {
+    constexpr int EPT = Elem<T>::kPer16;   // elements per thread per row
+    constexpr int TPR = D / EPT;           // threads per row
+    constexpr int RG = 256 / TPR;          // rows in flight
+    __shared__ double s_sum[RG][D];
+    const int k = blockIdx.x;
+    int h = blockIdx.y;
+    const T *X;
+    double *Xc;
+    int64_t s_l;
+    if (h < H_q) {
+        X = Q + (int64_t)h * qs_h; s_l = qs_l; Xc = Qc + ((int64_t)h * N_c + k) * D;
+    } else {
+        h -= H_q;
+        X = K + (int64_t)h * ks_h; s_l = ks_l; Xc = Kc + ((int64_t)h * N_c + k) * D;
+    }
+    const int b0 = B[k], b1 = B[k + 1];
+    const int tid = threadIdx.x;
+    const int rg = tid / TPR, col = (tid % TPR) * EPT;
+    double acc[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) acc[e] = 0.0;
+    for (int i = b0 + rg; i < b1; i += RG) {
+        uint4 u = *reinterpret_cast<const uint4 *>(X + (int64_t)i * s_l + col);
+        Elem<T>::unpack(u, acc);
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) s_sum[rg][col + e] = acc[e];
+    __syncthreads();
+    if (tid < D) {
+        double sum = 0.0;
+#pragma unroll 4
+        for (int r = 0; r < RG; ++r) sum += s_sum[r][tid];
+        double len = (double)(b1 - b0);
+        Xc[tid] = (sqrt(len) / len) * sum;
+    }
+}
+
+hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, double *Qc,
+                       double *Kc, hipStream_t s) {
+    dim3 grid(p.N_c, p.H_q + p.H_kv), block(256);
+#define DHSA_POOL(T, DD)                                                                                  \
+    hipLaunchKernelGGL((k_pool<T, DD>), grid, block, 0, s, (const T *)Q, (const T *)K, B_dev, Qc, Kc,     \
+                       p.H_q, p.N_c, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
+    if (p.dtype == DHSA_F32) {
+        if (p.D == 64) DHSA_POOL(float, 64); else DHSA_POOL(float, 128);
+    } else {
+        if (p.D == 64) DHSA_POOL(bf16_t, 64); else DHSA_POOL(bf16_t, 128);
+    }
+#undef DHSA_POOL
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Chunk similarity S_c[h, l, k] = <Q_c[h, l], K_c[h / G, k]> for k <= l, fp64
+// MFMA (16x16x4).  A 64 x 64 output tile per block; four waves in a 2 x 2
+// arrangement, each 32 x 32 = 2 x 2 MFMA blocks.  Tiles entirely above the
+// diagonal are skipped (those chunk pairs are never visible).
+// ---------------------------------------------------------------------------
+constexpr int kScTile = 64;
+constexpr int kScKc = 32;   // reduction slab staged in LDS
+constexpr int kScPad = 1;
+
+__global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, const double *__restrict__ Kc,
+                                                double *__restrict__ Sc, int N_c, int D, int G) {
+    const int k0 = blockIdx.x * kScTile, l0 = blockIdx.y * kScTile, h = blockIdx.z;
+    if (k0 > l0 + kScTile - 1) return;
+    __shared__ double sA[kScTile][kScKc + kScPad];
+    __shared__ double sB[kScTile][kScKc + kScPad];
+    const double *A = Qc + (int64_t)h * N_c * D;
+    const double *Bm = Kc + (int64_t)(h / G) * N_c * D;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wl = (wave >> 1) * 32, wk = (wave & 1) * 32;
+    f64x4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = (f64x4){0.0, 0.0, 0.0, 0.0};
+
+    for (int d0 = 0; d0 < D; d0 += kScKc) {
+        // stage 64 x 32 slabs of both operands (rows past N_c read as zero)
+        for (int x = tid; x < kScTile * kScKc; x += 256) {
+            int r = x / kScKc, c = x % kScKc;
+            sA[r][c] = (l0 + r < N_c) ? A[(int64_t)(l0 + r) * D + d0 + c] : 0.0;
+            sB[r][c] = (k0 + r < N_c) ? Bm[(int64_t)(k0 + r) * D + d0 + c] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kScKc; kk += 4) {
+            double a[2], b[2];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                a[m] = sA[wl + 16 * m + (lane & 15)][kk + (lane >> 4)];
+                b[m] = sB[wk + 16 * m + (lane & 15)][kk + (lane >> 4)];
+            }
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int n = 0; n < 2; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[m], b[n], acc[m][n], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // D[i][j]: accumulator element v of a lane is row 4*v + lane/16, column lane % 16
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                int l = l0 + wl + 16 * m + 4 * v + (lane >> 4);
+                int k = k0 + wk + 16 * n + (lane & 15);
+                if (l < N_c && k < N_c) Sc[((int64_t)h * N_c + l) * N_c + k] = acc[m][n][v];
+            }
+}
+
+hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, double *Sc, hipStream_t s) {
+    int nt = (p.N_c + kScTile - 1) / kScTile;
+    hipLaunchKernelGGL(k_scores, dim3(nt, nt, p.H_q), dim3(256), 0, s, Qc, Kc, Sc, p.N_c, p.D, p.G);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Ranking + per-row budget for one (head, query chunk l): Alg. 1's Argsort and
+// walk, done once for all rows of the chunk.
+//   1. keys 0..l -> LDS as order-preserving 64-bit integers (+ chunk id);
+//   2. bitonic sort, larger score first, equal scores lower id first;
+//   3. exclusive prefix sum of chunk lengths along the ranking, chunk l left out
+//      -> rem = N_b - (tokens of other chunks before this rank);
+//   4. a chunk is kept if some row takes a token of it; kept chunks are
+//      compacted in ascending chunk id (prefix sum of flags) into the plan.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
+                                                PlanLayout pl, int N_c, int N_b) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_wave[4];
+    __shared__ int s_p;
+    const int l = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int n = l + 1;
+    int P = 64;
+    while (P < n) P <<= 1;
+    unsigned long long *key = reinterpret_cast<unsigned long long *>(smem);  // [P]
+    int *id = reinterpret_cast<int *>(smem + (size_t)P * 8);                 // [P]
+    const int32_t *B = plan + pl.off_B;
+    const double *row = Sc + ((int64_t)h * N_c + l) * N_c;
+
+    for (int x = tid; x < P; x += 256) {
+        unsigned long long u = 0ull;
+        int k = 0x7fffffff;
+        if (x < n) {
+            double s = row[x];
+            if (s == 0.0) s = 0.0;  // -0.0 ties with +0.0
+            u = (unsigned long long)__double_as_longlong(s);
+            u = (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+            k = x;
+        }
+        key[x] = u;
+        id[x] = k;
+    }
+    __syncthreads();
+    // bitonic network; "a goes first" iff key larger, or equal and id smaller
+    for (int size = 2; size <= P; size <<= 1) {
+        for (int j = size >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (P >> 1); t += 256) {
+                int lo = ((t / j) * (j << 1)) + (t % j);
+                int hi = lo + j;
+                bool up = (lo & size) == 0;
+                unsigned long long ka = key[lo], kb = key[hi];
+                int ia = id[lo], ib = id[hi];
+                bool a_first = (ka > kb) || (ka == kb && ia < ib);
+                if (a_first != up) {
+                    key[lo] = kb; key[hi] = ka;
+                    id[lo] = ib; id[hi] = ia;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // rank of chunk l
+    for (int x = tid; x < n; x += 256)
+        if (id[x] == l) s_p = x;
+    __syncthreads();
+    const int p = s_p;
+    // the key array is dead now: reuse it as rem_by_id / pos_by_id
+    int *rem_by_id = reinterpret_cast<int *>(smem);        // [P]
+    int *pos_by_id = rem_by_id + P;                        // [P]
+    const int per = P / 256 > 0 ? P / 256 : 1;             // consecutive ranks per thread
+    {
+        int lens[32];
+        int local = 0;
+        for (int e = 0; e < per; ++e) {
+            int r = tid * per + e;
+            int len = 0;
+            if (r < n) {
+                int k = id[r];
+                len = (k == l) ? 0 : B[k + 1] - B[k];
+            }
+            lens[e] = len;
+            local += len;
+        }
+        int total;
+        int run = block_excl_scan(local, s_wave, &total);
+        __syncthreads();  // every thread has read its id[] and key[] is dead
+        for (int e = 0; e < per; ++e) {
+            int r = tid * per + e;
+            if (r < n) {
+                int k = id[r];
+                int pos = (r < p) ? 0 : (r == p ? 1 : 2);
+                int rem = N_b - run;                      // may be <= 0: not needed
+                bool need = (pos == 2) ? (rem > 1) : (rem > 0);
+                rem_by_id[k] = need ? rem : 0;
+                pos_by_id[k] = pos;
+            }
+            run += lens[e];
+        }
+    }
+    __syncthreads();
+    // compact in ascending chunk id
+    int32_t *entries = plan + pl.off_entries + ((int64_t)h * N_c + l) * pl.stride * 2;
+    {
+        int local = 0;
+        for (int e = 0; e < per; ++e) {
+            int k = tid * per + e;
+            if (k < n && rem_by_id[k] != 0) ++local;
+        }
+        int total;
+        int slot = block_excl_scan(local, s_wave, &total);
+        for (int e = 0; e < per; ++e) {
+            int k = tid * per + e;
+            if (k < n && rem_by_id[k] != 0) {
+                if (slot < pl.stride) {
+                    entries[2 * slot] = k | (pos_by_id[k] << kPosShift);
+                    entries[2 * slot + 1] = rem_by_id[k];
+                }
+                ++slot;
+            }
+        }
+        if (tid == 0) plan[pl.off_count + (int64_t)h * N_c + l] = total < pl.stride ? total : pl.stride;
+    }
+}
+
+hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s) {
+    int P = 64;
+    while (P < p.N_c) P <<= 1;
+    size_t shmem = (size_t)P * 12;
+    if (shmem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_select),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k_select, dim3(p.N_c, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Plan -> explicit index sets (Alg. 1's output) for a list of rows of one head.
+// One wave per row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_expand(PlanView pv, int N_c, int head, const int64_t *__restrict__ rows,
+                                               int32_t *__restrict__ idx, int cap, int32_t *__restrict__ cnt) {
+    const int t = blockIdx.x, lane = threadIdx.x;
+    const int64_t i = rows[t];
+    const int l = chunk_of_row(pv.B, N_c, i);
+    const int v = (int)(i + 1 - pv.B[l]);
+    const int E = pv.count[(int64_t)head * N_c + l];
+    const int32_t *ent = pv.entries + ((int64_t)head * N_c + l) * pv.stride * 2;
+    int32_t *out = idx + (int64_t)t * cap;
+    int n = 0;
+    for (int e = 0; e < E; ++e) {
+        int w0 = ent[2 * e], rem = ent[2 * e + 1];
+        int k = w0 & kChunkMask, pos = w0 >> kPosShift;
+        int b0 = pv.B[k];
+        int take = entry_take(pos, rem, pv.B[k + 1] - b0, v);
+        for (int x = lane; x < take; x += 64)
+            if (n + x < cap) out[n + x] = b0 + x;
+        n += take;
+    }
+    for (int x = n + lane; x < cap; x += 64) out[x] = -1;
+    if (lane == 0) cnt[t] = n;
+}
+
+hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
+                         int32_t *idx, int cap, int32_t *cnt, hipStream_t s) {
+    if (n_rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_expand, dim3(n_rows), dim3(64), 0, s, pv, p.N_c, head, rows_dev, idx, cap, cnt);
+    return hipGetLastError();
+}
+
+}  // namespace dhsa

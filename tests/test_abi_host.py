@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, sizes buffers sanely and rejects bad
+arguments before any device call."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_24606_amd as dhsa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dhsa.LIB_PATH):
+        from paper_2510_24606_amd import build
+        build.build()
+    return dhsa.lib()
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "dhsa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dhsa_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = header_symbols()
+    assert set(names) == set(dhsa.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert dhsa.dhsa_version() >= 100
+
+
+def mk(L=1000, H_q=4, H_kv=2, D=128, N_c=10, N_b=64, dtype=dhsa.DHSA_BF16, **kw):
+    return dhsa.dhsa_problem(L=L, H_q=H_q, H_kv=H_kv, D=D, N_c=N_c, N_b=N_b, dtype=dtype, **kw)
+
+
+def bounds(L=1000, N_c=10):
+    return np.linspace(0, L, N_c + 1).astype(np.int32)
+
+
+def test_sizes(lib):
+    B = bounds()
+    p = mk()
+    pb, wb = dhsa.dhsa_plan_bytes(p, B), dhsa.dhsa_workspace_bytes(p, B)
+    # workspace: pooled Q, K and S_c in fp64
+    assert wb >= 8 * (4 * 10 * 128 + 2 * 10 * 128 + 4 * 10 * 10)
+    # plan: header + B + counts + entries (stride <= N_c) + tiles
+    assert 64 + 4 * 11 + 4 * 40 <= pb <= 4 * (16 + 12 + 40 + 4 * 10 * 10 * 2 + 2 * 10 + 64 + 16)
+    # a tighter budget needs no more plan than a looser one
+    assert dhsa.dhsa_plan_bytes(mk(N_b=8), B) <= pb
+    # chunks longer than a row tile get several tiles
+    B2 = np.array([0, 1000], dtype=np.int32)
+    assert dhsa.dhsa_plan_bytes(mk(N_c=1), B2) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=7), 5),
+    (dict(L=0), 2),
+    (dict(H_q=5), 2),            # H_q % H_kv != 0
+    (dict(D=96), 2),
+    (dict(N_c=0), 2),
+    (dict(N_c=9000, L=20000), 2),  # above the chunk limit
+    (dict(N_b=0), 4),
+    (dict(scale=-1.0), 2),
+    (dict(q_stride_l=100), 2),   # row stride shorter than D
+    (dict(q_stride_l=132), 9),   # 264-byte rows break 16-byte alignment
+])
+def test_bad_problems_are_rejected_on_the_host(lib, kw, code):
+    p = mk(**kw)
+    B = bounds(L=max(p.L, 1), N_c=max(p.N_c, 1))
+    assert dhsa.dhsa_plan_bytes(p, B) == 0 and dhsa.dhsa_workspace_bytes(p, B) == 0
+    rc = lib.dhsa_route(C.byref(p), 16, 16, B.ctypes.data_as(C.POINTER(C.c_int32)), 16, 1 << 30, 16, 1 << 30, None)
+    assert rc == code, lib.dhsa_status_string(rc)
+
+
+def test_bad_boundaries_and_buffers(lib):
+    p = mk()
+    bp = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    for bad in (np.r_[1, bounds()[1:]], np.r_[bounds()[:-1], 999], np.r_[0, 100, 100, bounds()[3:]],
+                np.r_[0, 200, 100, bounds()[3:]]):
+        bad = bad.astype(np.int32)
+        assert lib.dhsa_route(C.byref(p), 16, 16, bp(bad), 16, 1 << 30, 16, 1 << 30, None) == 3
+        assert lib.dhsa_prefill(C.byref(p), 16, 16, 16, bp(bad), 16, 16, 1 << 30, 16, 1 << 30, None) == 3
+    B = bounds()
+    assert lib.dhsa_route(C.byref(p), None, 16, bp(B), 16, 1 << 30, 16, 1 << 30, None) == 1      # NULL
+    assert lib.dhsa_route(C.byref(p), 16, 16, None, 16, 1 << 30, 16, 1 << 30, None) == 1
+    assert lib.dhsa_route(C.byref(p), 16, 24, bp(B), 16, 1 << 30, 16, 1 << 30, None) == 9        # misaligned
+    assert lib.dhsa_route(C.byref(p), 16, 16, bp(B), 16, 8, 16, 1 << 30, None) == 6              # plan too small
+    assert lib.dhsa_route(C.byref(p), 16, 16, bp(B), 16, 1 << 30, 16, 8, None) == 6              # ws too small
+    assert lib.dhsa_sparse_prefill(C.byref(p), 16, 16, 16, bp(B), 16, 8, 16, None) == 8          # plan too small
+    assert lib.dhsa_prefill(C.byref(p), 16, 16, None, bp(B), 16, 16, 1 << 30, 16, 1 << 30, None) == 1
+    for s in range(10):
+        assert len(lib.dhsa_status_string(s)) > 1
+
+
+def test_no_oracle_in_the_product_path():
+    """The product package must not import, load or call the oracle."""
+    pkg = os.path.join(ROOT, "paper_2510_24606_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
