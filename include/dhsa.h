@@ -34,7 +34,8 @@
  *   - Every entry point returns a dhsa_status; arguments are validated before
  *     the first device call and on error nothing is written or launched.
  *   - Inputs must be finite; N_b > L behaves as N_b = L.
- *   - Limits: D in {64, 128}; 1 <= N_c <= 8192; L < 2^31.
+ *   - Limits: D in {64, 128}; 1 <= N_c <= 8192; L < 2^31; for DHSA_BF16 one K or V
+ *     head must span at most 4 GiB (L * row stride * 2 bytes).
  *   - Routing arithmetic (pooling, S_c, ranking) is fp64 so that the chosen
  *     index sets do not depend on summation order beyond ~1e-13 score gaps.
  *     Attention: DHSA_BF16 uses bf16 MFMA with fp32 softmax and accumulators

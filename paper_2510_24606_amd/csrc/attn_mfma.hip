@@ -5,9 +5,9 @@
 // chunk l.  All rows of the tile share the plan entries of (h, l); they differ
 // only through v = i + 1 - B[l].  The selected keys are walked in ascending
 // position (softmax is order-free) and packed densely into tiles of 64 keys;
-// a packed key carries (j, lo, hi) with "row takes key  <=>  lo < v < hi".
+// a packed key carries (row offset, lo, hi) with "row takes key <=> lo < v < hi".
 //
-// Four waves; wave w owns rows 32w .. 32w+31.  Scores are computed transposed,
+// Four waves; each owns one 32-row block.  Scores are computed transposed,
 // S^T = K Q^T (keys are the MFMA M dimension), so a lane holds 16 keys of ONE
 // query row per 32-key block: the row max / sum stay in the lane (one exchange
 // with lane ^ 32), and the exponentiated scores are already laid out as the B
@@ -20,10 +20,13 @@
 // 16-byte pieces of a row, applied through the choice of which piece each
 // lane fetches.
 //
-// Pipeline per key tile n (one barrier per tile): LDS buffer n%2 holds tile n;
-//   issue the loads of tile n+1 into buffer (n+1)%2;  every fourth tile each
-//   wave prepares the key list of one later tile;  MFMA + softmax on buffer
-//   n%2;  wait for the loads;  barrier
+// Pipeline, iteration n (one barrier per key tile; K(t), V(t) live in LDS
+// buffers t%2; work proceeds in 32-key blocks): issue the loads of the upper
+// half of K(n+1), of V(n+1) and of the lower half of K(n+2); every fourth tile
+// each wave prepares the key list of one later tile; then per block: the matrix
+// unit computes the scores of the NEXT block while the vector unit
+// exponentiates the current one, O += P V of the current block, mask and row
+// maximum of the next block; wait for the loads; barrier.
 #include <stdlib.h>
 
 #include "dhsa_internal.h"
@@ -33,7 +36,6 @@ namespace dhsa {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKT = 64;      // keys per tile
 constexpr int kSegB = 256;   // plan entries handled per batch
@@ -49,24 +51,28 @@ __device__ __forceinline__ int piece_swizzle(int r, int pieces_per_row) {
     return f;
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane L of the wave
-// writes bytes [16 L, 16 L + 16) of the window starting at `lds_window`, which
-// must be wave-uniform.  Completion is tracked by vmcnt.  (The builtin only
-// exists in the device pass.)
-__device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint16_t *lds_window) {
+// 16 bytes per lane from global memory (uniform base + per-lane 32-bit byte
+// offset) straight into LDS: lane L of the wave writes bytes [16 L, 16 L + 16)
+// of the window at LDS byte address `lds_window` (wave-uniform, goes through
+// M0, which nothing else in this kernel uses).  Completion is tracked by vmcnt;
+// the caller waits and then passes a
+// barrier before anyone reads the window.
+__device__ __forceinline__ void load16_to_lds(const char *base, unsigned byte_off, unsigned lds_window) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_window, 16, 0, 0);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_window) : "memory");
 #else
-    (void)g; (void)lds_window;
+    (void)base; (void)byte_off; (void)lds_window;
 #endif
 }
 
 template <int D>
 struct AttnSmem {
-    static constexpr int kTileBytes = kKT * D * 2;   // one K (or V) tile, rows unpadded
-    alignas(1024) uint16_t K[2][kKT * D];
-    alignas(1024) uint16_t V[2][kKT * D];
-    alignas(16) int key_j[8][kKT];
+    static constexpr int kTile = kKT * D;            // elements of one K (or V) tile, rows unpadded
+    alignas(1024) uint16_t K[2 * kTile];
+    alignas(1024) uint16_t V[2 * kTile];
+    alignas(16) unsigned key_koff[8][kKT];   // byte offset of the key's row in K / V of this kv-head
+    alignas(16) unsigned key_voff[8][kKT];
     alignas(16) int key_lo[8][kKT];
     alignas(16) int key_hi[8][kKT];
     alignas(16) int seg_start[kSegB + 16];
@@ -78,68 +84,54 @@ struct AttnSmem {
 };
 
 // blockIdx -> (head, tile).  Workgroups are dealt to the 8 XCDs round-robin and
-// each XCD has its own L2.  mode 0: one XCD serves the heads of one kv-group
-// and neighbouring row tiles (K/V slabs shared in that L2).  mode 1: plain
-// order, all XCDs on the same row tiles, heads fastest.  Tiles are issued from
-// the end of the sequence (most keys) to the start.
-__device__ __forceinline__ bool decode_block(int mode, int b, int H_q, int H_kv, int G, int T1, int *h,
-                                             int *tile) {
-    if (mode == 0 && H_kv % 8 == 0) {
-        const int x = b & 7, j = b >> 3;
-        const int s = j / (G * T1), r = j % (G * T1);
-        *tile = T1 - 1 - r / G;
-        *h = (x + 8 * s) * G + r % G;
-        return true;
-    }
-    if (mode == 0 && 8 % H_kv == 0) {
-        const int S = 8 / H_kv;
-        const int x = b & 7, j = b >> 3;
-        const int g = x % H_kv, s = x / H_kv;
-        const int rank = (j / G) * S + s;
-        if (rank >= T1) return false;
-        *tile = T1 - 1 - rank;
-        *h = g * G + j % G;
-        return true;
-    }
-    if (mode == 2) {  // kv-group major in time: every XCD works on the same kv-head
-        const int per = G * T1;
-        const int g = b / per, r = b % per;
-        *tile = T1 - 1 - r / G;
-        *h = g * G + r % G;
-        return true;
+// each XCD has its own L2.  `act` kv-heads (1, 2, 4 or 8) are worked on at a
+// time, each by 8 / act XCDs: act = 8 gives every XCD its own kv-head (best L2
+// reuse of the K/V slabs), smaller values keep fewer K/V slabs live at once
+// (they then fit the memory-side cache).  Within a kv-head, row tiles are
+// issued from the end of the sequence (most keys) to the start, the query heads
+// of the group innermost.  act = 0: plain order.
+__device__ __forceinline__ void decode_block(int act, int b, int H_q, int G, int T1, int *h, int *tile) {
+    if (act > 0) {
+        const int per = act * G * T1;          // workgroups per set of `act` kv-heads
+        const int p = b / per, r = b % per;
+        const int x = r & 7;
+        const int kv = p * act + (x & (act - 1));
+        const int idx = (r >> 3) * (8 / act) + x / act;
+        *tile = T1 - 1 - idx / G;
+        *h = kv * G + idx % G;
+        return;
     }
     *tile = T1 - 1 - b / H_q;
     *h = b % H_q;
-    return true;
 }
 
-static int attn_grid(int mode, int H_q, int H_kv, int G, int T1) {
-    if (mode == 0 && H_kv % 8 != 0 && 8 % H_kv == 0) {
-        const int S = 8 / H_kv;
-        return 8 * G * ((T1 + S - 1) / S);
-    }
-    return H_q * T1;
+// act must divide H_kv and act * G * T1 must be a multiple of 8 for the mapping above
+static int attn_order(int want, int H_kv, int G, int T1) {
+    for (int act = want; act >= 1; act >>= 1)
+        if (H_kv % act == 0 && (act * G * T1) % 8 == 0) return act;
+    return 0;
 }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_t *__restrict__ Q,
                                                       const uint16_t *__restrict__ K,
                                                       const uint16_t *__restrict__ V, uint16_t *__restrict__ O,
-                                                      int N_c, int H_q, int H_kv, int G, int mode,
+                                                      int N_c, int H_q, int G, int mode,
                                                       float scale_log2e, int64_t qs_h, int64_t qs_l,
                                                       int64_t ks_h, int64_t ks_l, int64_t vs_h, int64_t vs_l,
                                                       int64_t os_h, int64_t os_l) {
     using Smem = AttnSmem<D>;
     constexpr int OPR = D / 8;          // 16-byte pieces per row
-    constexpr int KPT = OPR / 4;        // pieces per thread per tile (K and V each)
+    constexpr int KPT = OPR / 4;        // load instructions per wave per tile (K and V each)
     constexpr int NS = D / 16;          // MFMA k-steps of Q K^T
     constexpr int NDB = D / 32;         // 32-wide output column blocks
+    constexpr int kTile = Smem::kTile;
     __shared__ Smem sm;
 
     int h, tile;
-    if (!decode_block(mode, blockIdx.x, H_q, H_kv, G, pv.T1, &h, &tile)) return;
+    decode_block(mode, blockIdx.x, H_q, G, pv.T1, &h, &tile);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform copy (LDS window base goes to M0)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform copy
     const int lr = lane & 31, g2 = lane >> 5;
     const int g = h / G;
     const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];
@@ -153,8 +145,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     const bool wave_live = rb * 32 < nrows;
     const int v_i = v_lo + rb * 32 + lr;  // this lane's query row (may be a padding row)
 
-    const uint16_t *Kg = K + (int64_t)g * ks_h;
-    const uint16_t *Vg = V + (int64_t)g * vs_h;
+    // K / V of this kv-head; rows are addressed by 32-bit byte offsets (the host
+    // checks that a head slab is below 4 GiB)
+    const char *Kg8 = reinterpret_cast<const char *>(K + (int64_t)g * ks_h);
+    const char *Vg8 = reinterpret_cast<const char *>(V + (int64_t)g * vs_h);
+    const unsigned k_row_bytes = (unsigned)ks_l * 2u, v_row_bytes = (unsigned)vs_l * 2u;
 
     // Q fragments: B operand of S^T = K Q^T; lane holds row lr, d = 16 s + 8 g2 .. + 7
     bf16x8 qf[NS];
@@ -171,36 +166,36 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_ref = -INFINITY, l_run = 0.f;   // m_ref: reference maximum used in the exponent (may lag the true maximum)
 
     const int E = pv.count[(int64_t)h * N_c + l];
     const int32_t *ent = pv.entries + ((int64_t)h * N_c + l) * pv.stride * 2;
 
     // staging: load instruction c of this wave fills LDS window (4 c + wave) of a
-    // tile (1 KiB = 64 pieces); this lane's piece there is row ld_row(c), physical
-    // piece lane % OPR, i.e. logical piece (lane % OPR) ^ swizzle(row)
+    // tile (1 KiB = 64 pieces); this lane's piece there is physical piece
+    // lane % OPR of row ld_row0 + 4 c RPW, i.e. logical piece (lane % OPR) ^
+    // swizzle(row) (the rows of one lane are 16 or 32 apart: same swizzle)
     constexpr int RPW = 64 / OPR;                                     // rows per window
-    const int ld_row0 = wave * RPW + lane / OPR;                      // + c * 4 * RPW
-    int ld_piece[KPT];
-#pragma unroll
-    for (int c = 0; c < KPT; ++c) ld_piece[c] = (lane % OPR) ^ piece_swizzle(ld_row0 + c * 4 * RPW, OPR);
+    const int ld_row0 = wave * RPW + lane / OPR;
+    const unsigned ld_piece_bytes = 16u * ((lane % OPR) ^ piece_swizzle(ld_row0, OPR));
+    const unsigned lds_K = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.K;
+    const unsigned lds_V = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.V;
     // operand fragments (element offsets inside a tile)
     //   K: row kb*32 + lr, logical piece 2 s + g2
-    //   V (transpose read): row kb*32 + 16 kk + 8 half + 4 g2 + c, elements db*32 + 16 dhalf + 4 r
     const int k_sw = piece_swizzle(lr, OPR);
-    int k_off[NS];
+    int k_off[NS];   // points into the K buffer of the current tile; moved once per tile
 #pragma unroll
     for (int s = 0; s < NS; ++s) k_off[s] = lr * D + 8 * ((2 * s + g2) ^ k_sw);
+    // Transpose-read source of this lane: row 8 half + 4 g2 + c of a 16-row group,
+    // logical piece P = 4 db + 2 dh + (r >> 1), physical piece P ^ swizzle(row).  The
+    // swizzle's bits 2-3 are (c >> 1) and half, so the physical piece is
+    //   low2 | 4 * (x2 ^ (c >> 1)),  x2 = db ^ 2 half (a compile-time value),
+    // and x2 ^ cb = x2 + cb for even x2, x2 - cb for odd x2: two per-lane bases,
+    // everything else folds into the instruction's immediate offset.
     const int tr_c = (lane & 15) >> 2, tr_r = lane & 3, tr_dh = (lane >> 4) & 1;
-    int v_off[2][NDB];
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const int row = 8 * half + 4 * g2 + tr_c;
-            const int piece = (4 * db + 2 * tr_dh + (tr_r >> 1)) ^ piece_swizzle(row, OPR);
-            v_off[half][db] = row * D + 8 * piece + 4 * (tr_r & 1);
-        }
+    const int tr_low2 = ((tr_r >> 1) ^ g2) | ((tr_dh ^ (tr_c & 1)) << 1);
+    const int tr_l0 = (4 * g2 + tr_c) * D + 8 * tr_low2 + 4 * (tr_r & 1);
+    int v_base_e = tr_l0 + 32 * (tr_c >> 1), v_base_o = tr_l0 - 32 * (tr_c >> 1);   // moved once per tile
 
     for (int e0 = 0; e0 < E; e0 += kSegB) {
         // ---- segment table of this batch of plan entries ----
@@ -220,11 +215,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
         sm.seg_start[tid] = start;                 // entries past the last segment hold `total`
         if (tid < 16) sm.seg_start[kSegB + tid] = total;
         __syncthreads();
-        const int nseg = (E - e0 < kSegB) ? E - e0 : kSegB;
         const int ntiles = (total + kKT - 1) / kKT;
         if (ntiles == 0) continue;
 
-// one wave: packed position -> (key index, lo, hi) of tile n.  The segment of a
+// one wave: packed position -> (row offsets, lo, hi) of tile n.  The segment of a
 // position is found with two 16-way steps over the sorted segment starts.
 #define DHSA_MAKE_META(n)                                                                       \
     {                                                                                           \
@@ -245,120 +239,172 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
         int lo_ = (pos_ == 1) ? t_ : 0;                                                         \
         int hi_ = (pos_ == 2) ? sm.seg_rem[seg_] - t_ : kIntMax;                                \
         if (pad_) { lo_ = kIntMax; hi_ = kIntMax; }                                             \
-        sm.key_j[buf_][lane] = sm.seg_b0[seg_] + t_;                                            \
+        const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
+        sm.key_koff[buf_][lane] = j_ * k_row_bytes;                                             \
+        sm.key_voff[buf_][lane] = j_ * v_row_bytes;                                             \
         sm.key_lo[buf_][lane] = lo_;                                                            \
         sm.key_hi[buf_][lane] = hi_;                                                            \
         const unsigned long long any_ = __ballot((lo_ >= v_lo) || (hi_ <= v_hi));               \
         if (lane == 0) sm.flags[buf_] = any_ != 0ull;                                           \
     }
-// issue the global -> LDS loads of tile n into buffer b (completion: vmcnt)
-#define DHSA_GLOAD(n, b)                                                                        \
+
+// issue the global -> LDS loads of windows c0..c1-1 of the K (or V) rows of tile n
+#define DHSA_GLOAD(lds_base, off_tab, base8, n, c0, c1)                                         \
     {                                                                                           \
         const int buf_ = (n) & 7;                                                               \
-        _Pragma("unroll") for (int c = 0; c < KPT; ++c) {                                       \
-            const int64_t j_ = sm.key_j[buf_][ld_row0 + c * 4 * RPW];                           \
-            const int win_ = (4 * c + wave_u) * 512;          /* window offset in elements */   \
-            load16_to_lds(Kg + j_ * ks_l + 8 * ld_piece[c], &sm.K[b][win_]);                    \
-            load16_to_lds(Vg + j_ * vs_l + 8 * ld_piece[c], &sm.V[b][win_]);                    \
+        const unsigned dst_ = lds_base + (((n) & 1) * kTile + wave_u * 512) * 2;                \
+        _Pragma("unroll") for (int c = c0; c < c1; ++c)                                         \
+            load16_to_lds(base8, sm.off_tab[buf_][ld_row0 + c * 4 * RPW] + ld_piece_bytes,      \
+                          dst_ + c * 4096);                                                     \
+    }
+#define DHSA_LOAD_K_LO(n) DHSA_GLOAD(lds_K, key_koff, Kg8, n, 0, KPT / 2)      /* keys 0..31  */
+#define DHSA_LOAD_K_HI(n) DHSA_GLOAD(lds_K, key_koff, Kg8, n, KPT / 2, KPT)    /* keys 32..63 */
+#define DHSA_LOAD_V(n) DHSA_GLOAD(lds_V, key_voff, Vg8, n, 0, KPT)
+
+// S^T of one 32-key block whose K rows start at element offset kb_off of the
+// buffer k_off points into: keys = MFMA rows, this lane's query row = column lr
+#define DHSA_QK(kb_off, sacc)                                                                   \
+    {                                                                                           \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) sacc[x] = 0.f;                           \
+        _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                        \
+            const bf16x8 kf_ = *reinterpret_cast<const bf16x8 *>(&sm.K[k_off[s] + (kb_off)]);   \
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf_, qf[s], sacc, 0, 0, 0);          \
         }                                                                                       \
     }
 
+// mask (only tiles that hold a key some row of the tile does not take) and row maximum
+#define DHSA_MASK_MAX(n, kb, sacc, mx)                                                          \
+    {                                                                                           \
+        const int buf_ = (n) & 7;                                                               \
+        if (sm.flags[buf_]) {                                                                   \
+            _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) {                                  \
+                const int key_ = (kb) * 32 + q4 * 8 + g2 * 4;                                   \
+                const int4 lo_ = *reinterpret_cast<const int4 *>(&sm.key_lo[buf_][key_]);       \
+                const int4 hi_ = *reinterpret_cast<const int4 *>(&sm.key_hi[buf_][key_]);       \
+                sacc[q4 * 4 + 0] = ((v_i > lo_.x) & (v_i < hi_.x)) ? sacc[q4 * 4 + 0] : -INFINITY; \
+                sacc[q4 * 4 + 1] = ((v_i > lo_.y) & (v_i < hi_.y)) ? sacc[q4 * 4 + 1] : -INFINITY; \
+                sacc[q4 * 4 + 2] = ((v_i > lo_.z) & (v_i < hi_.z)) ? sacc[q4 * 4 + 2] : -INFINITY; \
+                sacc[q4 * 4 + 3] = ((v_i > lo_.w) & (v_i < hi_.w)) ? sacc[q4 * 4 + 3] : -INFINITY; \
+            }                                                                                   \
+        }                                                                                       \
+        float m_ = sacc[0];                                                                     \
+        _Pragma("unroll") for (int x = 1; x < 16; ++x) m_ = fmaxf(m_, sacc[x]);                 \
+        mx = fmaxf(m_, __shfl_xor(m_, 32));                                                     \
+    }
+
+// The reference maximum m_ref of the exponent only moves when the block maximum
+// exceeds it by more than 2^8 in probability units, so exponentials stay <= 256
+// and the accumulators are rescaled on few blocks (O / l at the end is exact
+// whatever reference was used).
+#define DHSA_RESCALE(mx)                                                                        \
+    {                                                                                           \
+        const bool move_ = mx * scale_log2e > m_ref * scale_log2e + 8.f; /* false if mx = -inf */ \
+        if (__any(move_)) {                                                                     \
+            const float m_new_ = move_ ? mx : m_ref;                                            \
+            const float alpha_ = move_ ? __builtin_amdgcn_exp2f((m_ref - m_new_) * scale_log2e) : 1.f; \
+            l_run *= alpha_;                                                                    \
+            _Pragma("unroll") for (int db = 0; db < NDB; ++db)                                  \
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha_;           \
+            m_ref = m_new_;                                                                     \
+        }                                                                                       \
+    }
+
+// P = exp2(S * c - m_ref * c), row sum, rounded to the two bf16 MFMA B operands of the block
+#define DHSA_EXP(sacc, pf)                                                                      \
+    {                                                                                           \
+        const float mc_ = (m_ref == -INFINITY) ? 0.f : m_ref * scale_log2e;                     \
+        float psum_ = 0.f;                                                                      \
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                        \
+            const float e_ = __builtin_amdgcn_exp2f(sacc[x] * scale_log2e - mc_);               \
+            psum_ += e_;                                                                        \
+            pf[x >> 3][x & 7] = (__bf16)e_;                                                     \
+        }                                                                                       \
+        l_run += psum_;                                                                         \
+    }
+
+// O^T += V^T P^T for the 32-key block kb of the V buffer v_base_* point into
+#define DHSA_PV(kb, pf)                                                                         \
+    {                                                                                           \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                        \
+            _Pragma("unroll") for (int db = 0; db < NDB; ++db) {                                \
+                /* keys kb*32 + 16 kk + 4 g2 + {0..3} and the same + 8; columns db*32 + lr */   \
+                union { s16x4 h[2]; bf16x8 v; } vf_;                                            \
+                _Pragma("unroll") for (int half = 0; half < 2; ++half) {                        \
+                    const int x2_ = (OPR == 16) ? (db ^ (2 * half)) : db;                       \
+                    const uint16_t *vp_ = &sm.V[((x2_ & 1) ? v_base_o : v_base_e) +             \
+                                                ((kb) * 32 + 16 * kk + 8 * half) * D + 32 * x2_]; \
+                    vf_.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                      \
+                        (s16x4 __attribute__((address_space(3))) *)vp_);                        \
+                }                                                                               \
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_.v, pf[kk], oacc[db], 0, 0, 0); \
+            }                                                                                   \
+    }
+
+        // ---- prologue: key lists of tiles 0..3; K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
         if (wave < ntiles) DHSA_MAKE_META(wave);
         __syncthreads();
-        DHSA_GLOAD(0, 0);
+        DHSA_LOAD_K_LO(0);
+        DHSA_LOAD_K_HI(0);
+        DHSA_LOAD_V(0);
+        if (ntiles > 1) DHSA_LOAD_K_LO(1);
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's pieces are in LDS
         __syncthreads();
+        f32x16 s_a, s_b;                      // scores of the even / odd 32-key blocks
+        float mx_a = -INFINITY, mx_b = -INFINITY;
+        int toggle = kTile;                   // +tile, -tile, ...: k_off / v_base_* follow the current tile's buffer
+        if (wave_live) {
+            DHSA_QK(0, s_a);
+            DHSA_MASK_MAX(0, 0, s_a, mx_a);
+        }
+        __syncthreads();                      // the lower half of K(0) may be overwritten from here on
+
+        // ---- steady state, tile n: softmax and PV of its two blocks; the matrix unit
+        // computes the scores of the next block while the vector unit exponentiates ----
         for (int n = 0; n < ntiles; ++n) {
-            const int cur = n & 1;
-            if (n + 1 < ntiles) DHSA_GLOAD(n + 1, cur ^ 1);
+            const bool has_next = n + 1 < ntiles;
+            if (has_next) {
+                DHSA_LOAD_K_HI(n + 1);                     // over K(n-1), upper half
+                DHSA_LOAD_V(n + 1);                        // over V(n-1)
+                if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2); // over K(n), lower half
+            }
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
             if (wave_live) {
-                const int buf = n & 7;
-                const uint16_t *Ks = sm.K[cur];
-                const uint16_t *Vs = sm.V[cur];
-                // ---- S^T = K Q^T : two 32-key blocks ----
-                f32x16 sacc[2];
+                bf16x8 pf[2];
+                DHSA_RESCALE(mx_a);
+                DHSA_QK(32 * D, s_b);                      // block 1 of tile n
+                DHSA_EXP(s_a, pf);
+                DHSA_PV(0, pf);
+                DHSA_MASK_MAX(n, 1, s_b, mx_b);
+                DHSA_RESCALE(mx_b);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) sacc[kb][x] = 0.f;
-#pragma unroll
-                for (int s = 0; s < NS; ++s)
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb) {
-                        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[k_off[s] + kb * 32 * D]);
-                        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
-                    }
-                // ---- mask: key taken by this row iff lo < v_i < hi ----
-                if (sm.flags[buf]) {
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            const int key = kb * 32 + q4 * 8 + g2 * 4;
-                            const int4 lo = *reinterpret_cast<const int4 *>(&sm.key_lo[buf][key]);
-                            const int4 hi = *reinterpret_cast<const int4 *>(&sm.key_hi[buf][key]);
-                            sacc[kb][q4 * 4 + 0] = ((v_i > lo.x) & (v_i < hi.x)) ? sacc[kb][q4 * 4 + 0] : -INFINITY;
-                            sacc[kb][q4 * 4 + 1] = ((v_i > lo.y) & (v_i < hi.y)) ? sacc[kb][q4 * 4 + 1] : -INFINITY;
-                            sacc[kb][q4 * 4 + 2] = ((v_i > lo.z) & (v_i < hi.z)) ? sacc[kb][q4 * 4 + 2] : -INFINITY;
-                            sacc[kb][q4 * 4 + 3] = ((v_i > lo.w) & (v_i < hi.w)) ? sacc[kb][q4 * 4 + 3] : -INFINITY;
-                        }
-                }
-                // ---- online softmax (base 2), statistics per lane = per query row ----
-                float mx = -INFINITY;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[kb][x]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run, mx);
-                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                const float mc = m_use * scale_log2e;
-                if (__any(m_new != m_run)) {  // rescale only when some row's maximum moved
-                    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2e);
-                    l_run *= alpha;
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                        for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-                    m_run = m_new;
-                }
-                float psum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) {
-                        const float pexp = __builtin_amdgcn_exp2f(sacc[kb][x] * scale_log2e - mc);
-                        sacc[kb][x] = pexp;
-                        psum += pexp;
-                    }
-                l_run += psum;
-                // ---- O^T += V^T P^T ----
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int kk = 0; kk < 2; ++kk) {
-                        bf16x8 pf;
-#pragma unroll
-                        for (int x = 0; x < 8; ++x) pf[x] = (__bf16)sacc[kb][8 * kk + x];
-#pragma unroll
-                        for (int db = 0; db < NDB; ++db) {
-                            // keys kb*32 + 16 kk + 4 g2 + {0..3} and the same + 8; columns db*32 + lr
-                            const uint16_t *vb = &Vs[(kb * 32 + 16 * kk) * D];
-                            union { s16x4 h[2]; bf16x8 v; } vf;
-                            vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (s16x4 __attribute__((address_space(3))) *)(vb + v_off[0][db]));
-                            vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (s16x4 __attribute__((address_space(3))) *)(vb + v_off[1][db]));
-                            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[db], 0, 0, 0);
-                        }
-                    }
+                for (int s = 0; s < NS; ++s) k_off[s] += toggle;   // now the K buffer of tile n+1
+                if (has_next) DHSA_QK(0, s_a);             // block 0 of tile n+1
+                DHSA_EXP(s_b, pf);
+                DHSA_PV(1, pf);
+                if (has_next) DHSA_MASK_MAX(n + 1, 0, s_a, mx_a);
+                v_base_e += toggle;                        // now the V buffer of tile n+1
+                v_base_o += toggle;
+                toggle = -toggle;
             }
-            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the next tile's pieces have landed
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the pieces this wave requested have landed
             __syncthreads();
+        }
+        if (wave_live && (ntiles & 1)) {          // leave the offsets at buffer 0 for the next batch
+#pragma unroll
+            for (int s = 0; s < NS; ++s) k_off[s] -= kTile;
+            v_base_e -= kTile;
+            v_base_o -= kTile;
         }
 #undef DHSA_MAKE_META
 #undef DHSA_GLOAD
+#undef DHSA_LOAD_K_LO
+#undef DHSA_LOAD_K_HI
+#undef DHSA_LOAD_V
+#undef DHSA_QK
+#undef DHSA_MASK_MAX
+#undef DHSA_RESCALE
+#undef DHSA_EXP
+#undef DHSA_PV
     }
 
     // ---- epilogue: normalise, round to bf16, store ----
@@ -383,15 +429,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                             void *O, hipStream_t s) {
-    static const int mode = [] {
+    static const int want = [] {
         const char *e = getenv("DHSA_ATTN_ORDER");
-        return e ? atoi(e) : 2;
+        return e ? atoi(e) : 8;
     }();
-    const int grid = attn_grid(mode, p.H_q, p.H_kv, p.G, pv.T1);
+    const int mode = attn_order(want, p.H_kv, p.G, pv.T1);
+    const int grid = p.H_q * pv.T1;
     const float c = p.scale * 1.4426950408889634f;
 #define DHSA_MFMA(DD)                                                                                       \
     hipLaunchKernelGGL((k_attn_mfma<DD>), dim3(grid), dim3(256), 0, s, pv, (const uint16_t *)Q,             \
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, p.N_c, p.H_q, p.H_kv, p.G,  \
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, p.N_c, p.H_q, p.G,  \
                        mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l, p.os_h, p.os_l)
     if (p.D == 64) DHSA_MFMA(64); else DHSA_MFMA(128);
 #undef DHSA_MFMA

@@ -43,6 +43,9 @@ dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
         if (*s.out_l < row || *s.out_h < 0) return DHSA_ERR_SHAPE;
         if ((*s.out_l * esz) % 16 != 0 || (*s.out_h * esz) % 16 != 0) return DHSA_ERR_ALIGN;
     }
+    // the bf16 attention kernel addresses the rows of one K / V head with 32-bit byte offsets
+    if (in->dtype == DHSA_BF16 && (p->L * p->ks_l * 2 > ((int64_t)1 << 32) || p->L * p->vs_l * 2 > ((int64_t)1 << 32)))
+        return DHSA_ERR_SHAPE;
     return DHSA_OK;
 }
 
@@ -115,6 +118,7 @@ dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, 
 dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, const void *K, const void *V,
                         const void *plan, void *O, hipStream_t s) {
     const PlanView pv = plan_view(pl, plan);
+
     hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
                                           : launch_attn_rowwise(p, pv, Q, K, V, O, s);
     return hip_status(e);
