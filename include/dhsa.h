@@ -114,7 +114,7 @@ size_t dhsa_workspace_bytes(const dhsa_problem *prob, const int32_t *B_host);
 
 /* Steps 1-4 (Sec. 3.1, 3.3; Alg. 1): Q_dev, K_dev -> plan_dev.  ws_dev is
  * scratch (pooled vectors and S_c); its contents after the call are readable
- * through the dhsa_debug_* hooks until the next call that uses it. */
+ * through the dhsa_debug_* hooks until the next dhsa_route / dhsa_prefill on it. */
 dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
                        const int32_t *B_host, void *plan_dev, size_t plan_bytes, void *ws_dev,
                        size_t ws_bytes, void *stream);
@@ -122,10 +122,13 @@ dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *
 /* Step 5 (Alg. 2 / Alg. 3): exact softmax attention over the keys the plan
  * selects, O_dev[h, i, :] for every row.  The plan must come from dhsa_route on
  * the same problem and boundaries (it may be reused across calls, as the paper
- * caches routing results). */
+ * caches routing results).  ws_dev is a workspace of dhsa_workspace_bytes()
+ * (only its first 32 KiB are touched here: scheduling counters); calls that
+ * overlap in time must not share one. */
 dhsa_status dhsa_sparse_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
                                 const void *V_dev, const int32_t *B_host, const void *plan_dev,
-                                size_t plan_bytes, void *O_dev, void *stream);
+                                size_t plan_bytes, void *O_dev, void *ws_dev, size_t ws_bytes,
+                                void *stream);
 
 /* Steps 1-5 on one stream (Sec. 3.4 "Workflow"). */
 dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev,

@@ -55,7 +55,7 @@ def lib() -> C.CDLL:
         l.dhsa_workspace_bytes.argtypes = [P, i32p]; l.dhsa_workspace_bytes.restype = C.c_size_t
         l.dhsa_route.argtypes = [P, vp, vp, i32p, vp, C.c_size_t, vp, C.c_size_t, vp]
         l.dhsa_route.restype = C.c_int
-        l.dhsa_sparse_prefill.argtypes = [P, vp, vp, vp, i32p, vp, C.c_size_t, vp, vp]
+        l.dhsa_sparse_prefill.argtypes = [P, vp, vp, vp, i32p, vp, C.c_size_t, vp, vp, C.c_size_t, vp]
         l.dhsa_sparse_prefill.restype = C.c_int
         l.dhsa_prefill.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp, C.c_size_t, vp]
         l.dhsa_prefill.restype = C.c_int
@@ -131,11 +131,12 @@ def _with_vo(prob: dhsa_problem, V, O) -> dhsa_problem:
     return p
 
 
-def dhsa_sparse_prefill(prob, Q, K, V, B, plan, O) -> None:
+def dhsa_sparse_prefill(prob, Q, K, V, B, plan, O, ws) -> None:
     B = _b(B)
     p = _with_vo(prob, V, O)
     _check(lib().dhsa_sparse_prefill(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B),
-                                     plan.data_ptr(), plan.numel(), O.data_ptr(), _stream()))
+                                     plan.data_ptr(), plan.numel(), O.data_ptr(), ws.data_ptr(), ws.numel(),
+                                     _stream()))
 
 
 def dhsa_prefill(prob, Q, K, V, B, O, plan, ws) -> None:

@@ -40,6 +40,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kKT = 64;      // keys per tile
 constexpr int kSegB = 256;   // plan entries handled per batch
 constexpr int kIntMax = 0x7fffffff;
+#ifndef DHSA_FRAG_DEPTH
+#define DHSA_FRAG_DEPTH 3   // K fragments requested ahead of the MFMA that consumes them
+#endif
 
 // XOR swizzle of the 16-byte pieces of LDS row r (only r mod 16 matters).  Eight
 // (sixteen for 256-byte rows) consecutive rows get distinct values, so a column
@@ -65,6 +68,19 @@ __device__ __forceinline__ void load16_to_lds(const char *base, unsigned byte_of
     (void)base; (void)byte_off; (void)lds_window;
 #endif
 }
+
+// Arrive at a counter and wait (bounded) until `members` workgroups have.  Only
+// a pacing aid: nothing depends on the wait having succeeded.
+__device__ __forceinline__ void pace(int *ctr, int members) {
+    __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const long long t0 = wall_clock64();
+    while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < members &&
+           wall_clock64() - t0 < 5000) {   // 50 us at 100 MHz
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
+constexpr int kPhases = 8;   // pacing points per tile (the first at its start)
 
 template <int D>
 struct AttnSmem {
@@ -116,7 +132,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_t *__restrict__ Q,
                                                       const uint16_t *__restrict__ K,
                                                       const uint16_t *__restrict__ V, uint16_t *__restrict__ O,
-                                                      int N_c, int H_q, int G, int mode,
+                                                      int N_c, int H_q, int G, int mode, int n_virtual, int *__restrict__ sync_ctr,
                                                       float scale_log2e, int64_t qs_h, int64_t qs_l,
                                                       int64_t ks_h, int64_t ks_l, int64_t vs_h, int64_t vs_l,
                                                       int64_t os_h, int64_t os_l) {
@@ -128,11 +144,31 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     constexpr int kTile = Smem::kTile;
     __shared__ Smem sm;
 
-    int h, tile;
-    decode_block(mode, blockIdx.x, H_q, G, pv.T1, &h, &tile);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform copy
     const int lr = lane & 31, g2 = lane >> 5;
+
+    // Persistent workgroups: workgroup b takes the virtual blocks b, b + gridDim.x, ...
+    // (gridDim.x is a multiple of 8, so a workgroup stays on "its" XCD's share of
+    // the order).  With sync_ctr, the workgroups of one XCD start each round of
+    // tiles together: they then sweep the same K/V positions at the same time and
+    // share them in that XCD's L2.  The wait is bounded, so it only ever costs
+    // time: results do not depend on it.
+    for (int vb = blockIdx.x, round = 0; vb < n_virtual; vb += gridDim.x, ++round) {
+    int members = 0;
+    int *ctr = nullptr;
+    if (sync_ctr) {
+        const int x = blockIdx.x & 7;
+        const int first = round * (int)gridDim.x;                  // virtual blocks of this round
+        members = (n_virtual - first - x + 7) / 8;                 // ... that fall on this XCD
+        const int cap = (int)gridDim.x / 8;
+        if (members > cap) members = cap;
+        ctr = sync_ctr + (round * 8 + x) * kPhases;
+        if (tid == 0) pace(ctr, members);
+        __syncthreads();
+    }
+    int h, tile;
+    decode_block(mode, vb, H_q, G, pv.T1, &h, &tile);
     const int g = h / G;
     const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];
     const int b_l = pv.B[l];
@@ -141,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     const int v_lo = row0 + 1 - b_l, v_hi = v_lo + nrows - 1;
     // which 32-row block this wave owns: rotated per workgroup so that the waves
     // left without rows (short chunks) do not always sit on the same SIMD
-    const int rb = (wave + (blockIdx.x >> 3)) & 3;
+    const int rb = (wave + (vb >> 3)) & 3;
     const bool wave_live = rb * 32 < nrows;
     const int v_i = v_lo + rb * 32 + lr;  // this lane's query row (may be a padding row)
 
@@ -340,6 +376,26 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
             }                                                                                   \
     }
 
+// Instruction order wanted inside one block step (a hint to the scheduler): K
+// fragments fetched a few MFMAs ahead; between two MFMAs enough vector work
+// (exponentials, sums, conversions) to cover the MFMA's 32 cycles; the V
+// fragments of the PV product fetched while the last score MFMAs run.
+//   masks: 0x008 MFMA, 0x002 VALU, 0x100 LDS read
+#define DHSA_SCHED(depth)                                                                       \
+    {                                                                                           \
+        __builtin_amdgcn_sched_group_barrier(0x100, depth, 0);                                  \
+        _Pragma("unroll") for (int i_ = 0; i_ < NS; ++i_) {                                     \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                  \
+            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                                  \
+        }                                                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2 * NDB; ++i_) {                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                  \
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                                  \
+        }                                                                                       \
+    }
+
         // ---- prologue: key lists of tiles 0..3; K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
         if (wave < ntiles) DHSA_MAKE_META(wave);
         __syncthreads();
@@ -358,15 +414,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
         }
         __syncthreads();                      // the lower half of K(0) may be overwritten from here on
 
-        // ---- steady state, tile n: softmax and PV of its two blocks; the matrix unit
-        // computes the scores of the next block while the vector unit exponentiates ----
-        for (int n = 0; n < ntiles; ++n) {
-            const bool has_next = n + 1 < ntiles;
-            if (has_next) {
-                DHSA_LOAD_K_HI(n + 1);                     // over K(n-1), upper half
-                DHSA_LOAD_V(n + 1);                        // over V(n-1)
-                if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2); // over K(n), lower half
-            }
+        // ---- steady state, tile n (all but the last): softmax and PV of its two blocks; the
+        // matrix unit computes the scores of the next block while the vector unit exponentiates ----
+        int n = 0;
+        int phase = 1;                             // next pacing point of this tile
+        for (; n + 1 < ntiles; ++n) {
+            if (ctr && e0 == 0 && tid == 0)
+                while (phase < kPhases && n == phase * ntiles / kPhases) pace(ctr + phase++, members);
+            DHSA_LOAD_K_HI(n + 1);                     // over K(n-1), upper half
+            DHSA_LOAD_V(n + 1);                        // over V(n-1)
+            if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2); // over K(n), lower half
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
             if (wave_live) {
                 bf16x8 pf[2];
@@ -374,14 +431,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
                 DHSA_QK(32 * D, s_b);                      // block 1 of tile n
                 DHSA_EXP(s_a, pf);
                 DHSA_PV(0, pf);
+
                 DHSA_MASK_MAX(n, 1, s_b, mx_b);
                 DHSA_RESCALE(mx_b);
 #pragma unroll
                 for (int s = 0; s < NS; ++s) k_off[s] += toggle;   // now the K buffer of tile n+1
-                if (has_next) DHSA_QK(0, s_a);             // block 0 of tile n+1
+                DHSA_QK(0, s_a);                           // block 0 of tile n+1
                 DHSA_EXP(s_b, pf);
                 DHSA_PV(1, pf);
-                if (has_next) DHSA_MASK_MAX(n + 1, 0, s_a, mx_a);
+
+                DHSA_MASK_MAX(n + 1, 0, s_a, mx_a);
                 v_base_e += toggle;                        // now the V buffer of tile n+1
                 v_base_o += toggle;
                 toggle = -toggle;
@@ -389,7 +448,20 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the pieces this wave requested have landed
             __syncthreads();
         }
-        if (wave_live && (ntiles & 1)) {          // leave the offsets at buffer 0 for the next batch
+        // ---- last tile of the batch: nothing left to load or to score ahead ----
+        if (wave_live) {
+            bf16x8 pf[2];
+            DHSA_RESCALE(mx_a);
+            DHSA_QK(32 * D, s_b);
+            DHSA_EXP(s_a, pf);
+            DHSA_PV(0, pf);
+            DHSA_MASK_MAX(n, 1, s_b, mx_b);
+            DHSA_RESCALE(mx_b);
+            DHSA_EXP(s_b, pf);
+            DHSA_PV(1, pf);
+        }
+        __syncthreads();                          // LDS is reused by the next batch
+        if (wave_live && !(ntiles & 1)) {         // leave the offsets at buffer 0 for the next batch
 #pragma unroll
             for (int s = 0; s < NS; ++s) k_off[s] -= kTile;
             v_base_e -= kTile;
@@ -405,6 +477,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
 #undef DHSA_RESCALE
 #undef DHSA_EXP
 #undef DHSA_PV
+#undef DHSA_SCHED
     }
 
     // ---- epilogue: normalise, round to bf16, store ----
@@ -425,21 +498,56 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
                 }
         }
     }
+    __syncthreads();   // LDS is reused by the next tile of this workgroup
+    }  // persistent loop
+}
+
+// zero the round counters of the persistent kernel
+__global__ void k_zero(int *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
-                            void *O, hipStream_t s) {
+                            void *O, int *sync_ctr, int sync_ints, hipStream_t s) {
     static const int want = [] {
         const char *e = getenv("DHSA_ATTN_ORDER");
         return e ? atoi(e) : 8;
     }();
+    static const int persist = [] {
+        const char *e = getenv("DHSA_ATTN_PERSIST");
+        return e ? atoi(e) : 0;
+    }();
     const int mode = attn_order(want, p.H_kv, p.G, pv.T1);
-    const int grid = p.H_q * pv.T1;
+    const int n_virtual = p.H_q * pv.T1;
+    int grid = n_virtual;
+    int *ctr = nullptr;
+    if (persist && mode > 0) {
+        // as many workgroups as the chip holds at once
+        int dev = 0, cus = 0, occ = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = (p.D == 64) ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn_mfma<64>, 256, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn_mfma<128>, 256, 0);
+        if (e != hipSuccess) return e;
+        const int resident = cus * occ / 8 * 8;
+        if (resident >= 8 && resident < n_virtual) {
+            grid = resident;
+            const int rounds = (n_virtual + grid - 1) / grid;
+            const int ints = rounds * 8 * kPhases;
+            if (persist == 1 && sync_ctr && ints <= sync_ints) {
+                ctr = sync_ctr;
+                hipLaunchKernelGGL(k_zero, dim3((ints + 255) / 256), dim3(256), 0, s, ctr, ints);
+            }
+        }
+    }
     const float c = p.scale * 1.4426950408889634f;
 #define DHSA_MFMA(DD)                                                                                       \
     hipLaunchKernelGGL((k_attn_mfma<DD>), dim3(grid), dim3(256), 0, s, pv, (const uint16_t *)Q,             \
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, p.N_c, p.H_q, p.G,  \
-                       mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l, p.os_h, p.os_l)
+                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, p.N_c, p.H_q, p.G,          \
+                       mode, n_virtual, ctr, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l, p.os_h,     \
+                       p.os_l)
     if (p.D == 64) DHSA_MFMA(64); else DHSA_MFMA(128);
 #undef DHSA_MFMA
     return hipGetLastError();

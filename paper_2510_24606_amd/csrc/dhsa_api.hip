@@ -78,7 +78,8 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
 
 WsLayout ws_layout(const Prob &p) {
     WsLayout w;
-    w.off_Qc = 0;
+    w.off_sync = 0;                                  // kSyncInts ints: round counters of the attention kernel
+    w.off_Qc = kSyncInts / 2;
     w.off_Kc = align_up(w.off_Qc + (int64_t)p.H_q * p.N_c * p.D, 32);
     w.off_Sc = align_up(w.off_Kc + (int64_t)p.H_kv * p.N_c * p.D, 32);
     w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_c * p.N_c, 32);
@@ -115,11 +116,12 @@ dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, 
     return DHSA_OK;
 }
 
-dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, const void *K, const void *V,
-                        const void *plan, void *O, hipStream_t s) {
+dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, const void *Q, const void *K,
+                        const void *V, const void *plan, void *O, void *ws, hipStream_t s) {
     const PlanView pv = plan_view(pl, plan);
+    int *sync_ctr = reinterpret_cast<int *>(static_cast<double *>(ws) + wl.off_sync);
 
-    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
+    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, sync_ctr, kSyncInts, s)
                                           : launch_attn_rowwise(p, pv, Q, K, V, O, s);
     return hip_status(e);
 }
@@ -160,16 +162,20 @@ __attribute__((visibility("default"))) dhsa_status dhsa_sparse_prefill(const dhs
                                                                        const void *K_dev, const void *V_dev,
                                                                        const int32_t *B_host, const void *plan_dev,
                                                                        size_t plan_bytes, void *O_dev,
+                                                                       void *ws_dev, size_t ws_bytes,
                                                                        void *stream) {
     Prob p;
     dhsa_status st = resolve(prob, B_host, &p);
     if (st != DHSA_OK) return st;
-    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev) return DHSA_ERR_NULL;
-    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) || misaligned(O_dev))
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev || !ws_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) ||
+        misaligned(O_dev) || misaligned(ws_dev))
         return DHSA_ERR_ALIGN;
     const PlanLayout pl = plan_layout(p, B_host);
+    const WsLayout wl = ws_layout(p);
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
-    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, static_cast<hipStream_t>(stream));
+    if (ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
+    return attend_impl(p, pl, wl, Q_dev, K_dev, V_dev, plan_dev, O_dev, ws_dev, static_cast<hipStream_t>(stream));
 }
 
 __attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev,
@@ -190,7 +196,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_probl
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, s);
     if (st != DHSA_OK) return st;
-    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
+    return attend_impl(p, pl, wl, Q_dev, K_dev, V_dev, plan_dev, O_dev, ws_dev, s);
 }
 
 __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(

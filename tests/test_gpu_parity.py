@@ -140,8 +140,8 @@ def test_route_then_sparse_prefill_equals_prefill_and_is_deterministic():
     plan, ws = dhsa.alloc(g1["prob"], w.B)
     dhsa.dhsa_route(g1["prob"], g1["Q"], g1["K"], w.B, plan, ws)
     O = torch.zeros_like(g1["Q"])
-    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O)
-    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O)   # the plan is reusable
+    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O, ws)
+    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O, ws)   # the plan is reusable
     torch.cuda.synchronize()
     assert plans_equal(plan, g1["plan"])
     assert torch.equal(O.view(torch.int16), g1["O"].view(torch.int16))
