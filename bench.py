@@ -62,7 +62,7 @@ def main() -> int:
         dhsa.dhsa_route(prob, Q, K, w.B, plan, ws)
         if ev is not None:
             ev[0].record()
-        dhsa.dhsa_sparse_prefill(prob, Q, K, V, w.B, plan, O, ws)
+        dhsa.dhsa_sparse_prefill(prob, Q, K, V, w.B, plan, O)
         if ev is not None:
             ev[1].record()
 

@@ -89,7 +89,7 @@ typedef struct {
  * their own chunk.
  *   words [0, 16)            header: magic 'DHSA', version, H_q, N_c, N_b (clamped to L),
  *                            stride, L, T1 (row tiles per head), off_B, off_count,
- *                            off_entries, off_tiles (word offsets), rest 0
+ *                            off_entries, off_tiles (word offsets), T_big, rest 0
  *   off_B      int32[N_c+1]  the boundaries
  *   off_count  int32[H_q][N_c]          number of entries of (h, l)
  *   off_entries int32[H_q][N_c][stride][2]   entries, ascending chunk id:
@@ -102,7 +102,8 @@ typedef struct {
  *        t < min(len_k, rem - v)        if pos = 2
  *      Only chunks some row of l takes a token from are listed.
  *   off_tiles  int32[T1][2]  row tiles of one head: (chunk l, first row), rows
- *                            [row, min(row + 128, B[l+1])), ordered by row
+ *                            [row, min(row + 128, B[l+1])); first the T_big tiles of
+ *                            more than 64 rows, then the others, each group by row
  */
 #define DHSA_PLAN_MAGIC 0x41534844
 #define DHSA_PLAN_VERSION 1
@@ -114,7 +115,7 @@ size_t dhsa_workspace_bytes(const dhsa_problem *prob, const int32_t *B_host);
 
 /* Steps 1-4 (Sec. 3.1, 3.3; Alg. 1): Q_dev, K_dev -> plan_dev.  ws_dev is
  * scratch (pooled vectors and S_c); its contents after the call are readable
- * through the dhsa_debug_* hooks until the next dhsa_route / dhsa_prefill on it. */
+ * through the dhsa_debug_* hooks until the next call that uses it. */
 dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
                        const int32_t *B_host, void *plan_dev, size_t plan_bytes, void *ws_dev,
                        size_t ws_bytes, void *stream);
@@ -122,13 +123,10 @@ dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *
 /* Step 5 (Alg. 2 / Alg. 3): exact softmax attention over the keys the plan
  * selects, O_dev[h, i, :] for every row.  The plan must come from dhsa_route on
  * the same problem and boundaries (it may be reused across calls, as the paper
- * caches routing results).  ws_dev is a workspace of dhsa_workspace_bytes()
- * (only its first 32 KiB are touched here: scheduling counters); calls that
- * overlap in time must not share one. */
+ * caches routing results). */
 dhsa_status dhsa_sparse_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
                                 const void *V_dev, const int32_t *B_host, const void *plan_dev,
-                                size_t plan_bytes, void *O_dev, void *ws_dev, size_t ws_bytes,
-                                void *stream);
+                                size_t plan_bytes, void *O_dev, void *stream);
 
 /* Steps 1-5 on one stream (Sec. 3.4 "Workflow"). */
 dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev,

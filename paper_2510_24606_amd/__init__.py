@@ -55,7 +55,7 @@ def lib() -> C.CDLL:
         l.dhsa_workspace_bytes.argtypes = [P, i32p]; l.dhsa_workspace_bytes.restype = C.c_size_t
         l.dhsa_route.argtypes = [P, vp, vp, i32p, vp, C.c_size_t, vp, C.c_size_t, vp]
         l.dhsa_route.restype = C.c_int
-        l.dhsa_sparse_prefill.argtypes = [P, vp, vp, vp, i32p, vp, C.c_size_t, vp, vp, C.c_size_t, vp]
+        l.dhsa_sparse_prefill.argtypes = [P, vp, vp, vp, i32p, vp, C.c_size_t, vp, vp]
         l.dhsa_sparse_prefill.restype = C.c_int
         l.dhsa_prefill.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp, C.c_size_t, vp]
         l.dhsa_prefill.restype = C.c_int
@@ -131,12 +131,11 @@ def _with_vo(prob: dhsa_problem, V, O) -> dhsa_problem:
     return p
 
 
-def dhsa_sparse_prefill(prob, Q, K, V, B, plan, O, ws) -> None:
+def dhsa_sparse_prefill(prob, Q, K, V, B, plan, O) -> None:
     B = _b(B)
     p = _with_vo(prob, V, O)
     _check(lib().dhsa_sparse_prefill(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B),
-                                     plan.data_ptr(), plan.numel(), O.data_ptr(), ws.data_ptr(), ws.numel(),
-                                     _stream()))
+                                     plan.data_ptr(), plan.numel(), O.data_ptr(), _stream()))
 
 
 def dhsa_prefill(prob, Q, K, V, B, O, plan, ws) -> None:
@@ -184,7 +183,7 @@ def parse_plan(plan_host: np.ndarray) -> dict:
     assert w[0] == PLAN_MAGIC, "not a DHSA plan"
     H_q, N_c, N_b, stride, L, T1 = (int(x) for x in (w[2], w[3], w[4], w[5], w[6], w[7]))
     oB, oC, oE, oT = (int(x) for x in w[8:12])
-    return dict(H_q=H_q, N_c=N_c, N_b=N_b, stride=stride, L=L, T1=T1,
+    return dict(H_q=H_q, N_c=N_c, N_b=N_b, stride=stride, L=L, T1=T1, T_big=int(w[12]),
                 B=w[oB:oB + N_c + 1],
                 count=w[oC:oC + H_q * N_c].reshape(H_q, N_c),
                 entries=w[oE:oE + H_q * N_c * stride * 2].reshape(H_q, N_c, stride, 2),

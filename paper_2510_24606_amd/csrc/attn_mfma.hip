@@ -69,19 +69,6 @@ __device__ __forceinline__ void load16_to_lds(const char *base, unsigned byte_of
 #endif
 }
 
-// Arrive at a counter and wait (bounded) until `members` workgroups have.  Only
-// a pacing aid: nothing depends on the wait having succeeded.
-__device__ __forceinline__ void pace(int *ctr, int members) {
-    __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const long long t0 = wall_clock64();
-    while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < members &&
-           wall_clock64() - t0 < 5000) {   // 50 us at 100 MHz
-        __builtin_amdgcn_s_sleep(8);
-    }
-}
-
-constexpr int kPhases = 8;   // pacing points per tile (the first at its start)
-
 template <int D>
 struct AttnSmem {
     static constexpr int kTile = kKT * D;            // elements of one K (or V) tile, rows unpadded
@@ -128,11 +115,11 @@ static int attn_order(int want, int H_kv, int G, int T1) {
     return 0;
 }
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_t *__restrict__ Q,
+template <int D, bool PAR>
+__global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, int T, const uint16_t *__restrict__ Q,
                                                       const uint16_t *__restrict__ K,
                                                       const uint16_t *__restrict__ V, uint16_t *__restrict__ O,
-                                                      int N_c, int H_q, int G, int mode, int n_virtual, int *__restrict__ sync_ctr,
+                                                      int N_c, int H_q, int G, int mode,
                                                       float scale_log2e, int64_t qs_h, int64_t qs_l,
                                                       int64_t ks_h, int64_t ks_l, int64_t vs_h, int64_t vs_l,
                                                       int64_t os_h, int64_t os_l) {
@@ -148,36 +135,24 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform copy
     const int lr = lane & 31, g2 = lane >> 5;
 
-    // Persistent workgroups: workgroup b takes the virtual blocks b, b + gridDim.x, ...
-    // (gridDim.x is a multiple of 8, so a workgroup stays on "its" XCD's share of
-    // the order).  With sync_ctr, the workgroups of one XCD start each round of
-    // tiles together: they then sweep the same K/V positions at the same time and
-    // share them in that XCD's L2.  The wait is bounded, so it only ever costs
-    // time: results do not depend on it.
-    for (int vb = blockIdx.x, round = 0; vb < n_virtual; vb += gridDim.x, ++round) {
-    int members = 0;
-    int *ctr = nullptr;
-    if (sync_ctr) {
-        const int x = blockIdx.x & 7;
-        const int first = round * (int)gridDim.x;                  // virtual blocks of this round
-        members = (n_virtual - first - x + 7) / 8;                 // ... that fall on this XCD
-        const int cap = (int)gridDim.x / 8;
-        if (members > cap) members = cap;
-        ctr = sync_ctr + (round * 8 + x) * kPhases;
-        if (tid == 0) pace(ctr, members);
-        __syncthreads();
-    }
     int h, tile;
-    decode_block(mode, vb, H_q, G, pv.T1, &h, &tile);
+    decode_block(mode, blockIdx.x, H_q, G, T, &h, &tile);
+    tile += tile0;   // this launch covers tiles [tile0, tile0 + T) of the plan's table
     const int g = h / G;
     const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];
     const int b_l = pv.B[l];
     const int rows_left = pv.B[l + 1] - row0;
     const int nrows = rows_left < kRowTile ? rows_left : kRowTile;
     const int v_lo = row0 + 1 - b_l, v_hi = v_lo + nrows - 1;
-    // which 32-row block this wave owns: rotated per workgroup so that the waves
-    // left without rows (short chunks) do not always sit on the same SIMD
-    const int rb = (wave + (vb >> 3)) & 3;
+    // Wave roles (PAR = false / true is chosen per launch: the plan lists the tiles
+    // of more than 64 rows first).  Tiles of more than 64 rows: wave = one 32-row block (rotated per
+    // workgroup so that the waves left without rows do not always sit on the same
+    // SIMD), both 32-key blocks of every key tile.  Tiles of at most 64 rows: two
+    // waves per row block, each taking ONE of the two 32-key blocks of every key
+    // tile ("key parity" kbw); their partial softmax states are merged at the end.
+    constexpr bool par = PAR;
+    const int rb = par ? (wave & 1) : ((wave + (blockIdx.x >> 3)) & 3);
+    const int kbw = par ? (wave >> 1) : 0;
     const bool wave_live = rb * 32 < nrows;
     const int v_i = v_lo + rb * 32 + lr;  // this lane's query row (may be a padding row)
 
@@ -221,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     const int k_sw = piece_swizzle(lr, OPR);
     int k_off[NS];   // points into the K buffer of the current tile; moved once per tile
 #pragma unroll
-    for (int s = 0; s < NS; ++s) k_off[s] = lr * D + 8 * ((2 * s + g2) ^ k_sw);
+    for (int s = 0; s < NS; ++s) k_off[s] = (kbw * 32 + lr) * D + 8 * ((2 * s + g2) ^ k_sw);
     // Transpose-read source of this lane: row 8 half + 4 g2 + c of a 16-row group,
     // logical piece P = 4 db + 2 dh + (r >> 1), physical piece P ^ swizzle(row).  The
     // swizzle's bits 2-3 are (c >> 1) and half, so the physical piece is
@@ -231,7 +206,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
     const int tr_c = (lane & 15) >> 2, tr_r = lane & 3, tr_dh = (lane >> 4) & 1;
     const int tr_low2 = ((tr_r >> 1) ^ g2) | ((tr_dh ^ (tr_c & 1)) << 1);
     const int tr_l0 = (4 * g2 + tr_c) * D + 8 * tr_low2 + 4 * (tr_r & 1);
-    int v_base_e = tr_l0 + 32 * (tr_c >> 1), v_base_o = tr_l0 - 32 * (tr_c >> 1);   // moved once per tile
+    int v_base_e = kbw * 32 * D + tr_l0 + 32 * (tr_c >> 1);   // moved once per tile
+    int v_base_o = kbw * 32 * D + tr_l0 - 32 * (tr_c >> 1);
 
     for (int e0 = 0; e0 < E; e0 += kSegB) {
         // ---- segment table of this batch of plan entries ----
@@ -396,18 +372,20 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
         }                                                                                       \
     }
 
-        // ---- prologue: key lists of tiles 0..3; K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
-        if (wave < ntiles) DHSA_MAKE_META(wave);
+        f32x16 s_a, s_b;                      // scores of two consecutive blocks (ping-pong)
+        float mx_a = -INFINITY, mx_b = -INFINITY;
+        int toggle = kTile;                   // +tile, -tile, ...: k_off / v_base_* follow the tile buffers
+        if (wave < ntiles) DHSA_MAKE_META(wave);   // key lists of tiles 0..3
         __syncthreads();
+        if constexpr (!PAR) {
+        // ================= tiles of more than 64 rows =================
+        // ---- prologue: K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
         DHSA_LOAD_K_LO(0);
         DHSA_LOAD_K_HI(0);
         DHSA_LOAD_V(0);
         if (ntiles > 1) DHSA_LOAD_K_LO(1);
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's pieces are in LDS
         __syncthreads();
-        f32x16 s_a, s_b;                      // scores of the even / odd 32-key blocks
-        float mx_a = -INFINITY, mx_b = -INFINITY;
-        int toggle = kTile;                   // +tile, -tile, ...: k_off / v_base_* follow the current tile's buffer
         if (wave_live) {
             DHSA_QK(0, s_a);
             DHSA_MASK_MAX(0, 0, s_a, mx_a);
@@ -417,10 +395,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
         // ---- steady state, tile n (all but the last): softmax and PV of its two blocks; the
         // matrix unit computes the scores of the next block while the vector unit exponentiates ----
         int n = 0;
-        int phase = 1;                             // next pacing point of this tile
         for (; n + 1 < ntiles; ++n) {
-            if (ctr && e0 == 0 && tid == 0)
-                while (phase < kPhases && n == phase * ntiles / kPhases) pace(ctr + phase++, members);
             DHSA_LOAD_K_HI(n + 1);                     // over K(n-1), upper half
             DHSA_LOAD_V(n + 1);                        // over V(n-1)
             if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2); // over K(n), lower half
@@ -431,7 +406,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
                 DHSA_QK(32 * D, s_b);                      // block 1 of tile n
                 DHSA_EXP(s_a, pf);
                 DHSA_PV(0, pf);
-
                 DHSA_MASK_MAX(n, 1, s_b, mx_b);
                 DHSA_RESCALE(mx_b);
 #pragma unroll
@@ -439,7 +413,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
                 DHSA_QK(0, s_a);                           // block 0 of tile n+1
                 DHSA_EXP(s_b, pf);
                 DHSA_PV(1, pf);
-
                 DHSA_MASK_MAX(n + 1, 0, s_a, mx_a);
                 v_base_e += toggle;                        // now the V buffer of tile n+1
                 v_base_o += toggle;
@@ -467,6 +440,65 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
             v_base_e -= kTile;
             v_base_o -= kTile;
         }
+        } else {
+        // ================= tiles of at most 64 rows: one 32-key block per wave and tile =================
+        // ---- prologue: K(0), V(0), K(1) in LDS; S(0, own block) ----
+        DHSA_LOAD_K_LO(0);
+        DHSA_LOAD_K_HI(0);
+        DHSA_LOAD_V(0);
+        if (ntiles > 1) { DHSA_LOAD_K_LO(1); DHSA_LOAD_K_HI(1); }
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        __syncthreads();
+        if (wave_live) {
+            DHSA_QK(0, s_a);
+            DHSA_MASK_MAX(0, kbw, s_a, mx_a);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) k_off[s] += kTile;   // K offsets run one tile ahead of V offsets
+        }
+        __syncthreads();                      // K(0) may be overwritten from here on
+
+        // ---- tile n (all but the last): softmax and PV of this wave's block (scores in s_a)
+        // while the matrix unit computes the scores of its block of tile n+1 (into s_b) ----
+        int n = 0;
+        for (; n + 1 < ntiles; ++n) {
+            if (n + 2 < ntiles) { DHSA_LOAD_K_LO(n + 2); DHSA_LOAD_K_HI(n + 2); }   // over K(n)
+            DHSA_LOAD_V(n + 1);                                                    // over V(n-1)
+            if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
+            if (wave_live) {
+                bf16x8 pf[2];
+                DHSA_RESCALE(mx_a);
+                DHSA_QK(0, s_b);
+                DHSA_EXP(s_a, pf);
+                DHSA_PV(0, pf);
+                DHSA_MASK_MAX(n + 1, kbw, s_b, mx_b);
+                s_a = s_b;
+                mx_a = mx_b;
+#pragma unroll
+                for (int s = 0; s < NS; ++s) k_off[s] -= toggle;
+                v_base_e += toggle;
+                v_base_o += toggle;
+                toggle = -toggle;
+            }
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+            __syncthreads();
+        }
+        if (wave_live) {                          // last tile of the batch
+            bf16x8 pf[2];
+            DHSA_RESCALE(mx_a);
+            DHSA_EXP(s_a, pf);
+            DHSA_PV(0, pf);
+        }
+        __syncthreads();                          // LDS is reused by the next batch / the merge
+        if (wave_live) {                          // leave the offsets at buffer 0 for the next batch
+            if (ntiles & 1) {
+#pragma unroll
+                for (int s = 0; s < NS; ++s) k_off[s] -= kTile;
+            } else {
+                v_base_e -= kTile;
+                v_base_o -= kTile;
+            }
+        }
+        }
 #undef DHSA_MAKE_META
 #undef DHSA_GLOAD
 #undef DHSA_LOAD_K_LO
@@ -480,8 +512,33 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
 #undef DHSA_SCHED
     }
 
+    // ---- key-parity tiles: fold the state of the wave that took the odd blocks into its partner ----
+    if constexpr (PAR) {
+        float *xch = reinterpret_cast<float *>(sm.K) + rb * (NDB * 16 + 2) * 64 + lane;   // [slot][lane]
+        if (wave_live && kbw == 1) {
+            xch[0] = m_ref;
+            xch[64] = l_run;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) xch[(2 + db * 16 + x) * 64] = oacc[db][x];
+        }
+        __syncthreads();
+        if (wave_live && kbw == 0) {
+            const float m1 = xch[0], l1 = xch[64];
+            const float mm = fmaxf(m_ref, m1);
+            const float a0 = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mm) * scale_log2e);
+            const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - mm) * scale_log2e);
+            l_run = l_run * a0 + l1 * a1;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) oacc[db][x] = oacc[db][x] * a0 + xch[(2 + db * 16 + x) * 64] * a1;
+        }
+    }
+
     // ---- epilogue: normalise, round to bf16, store ----
-    if (wave_live) {
+    if (wave_live && kbw == 0) {
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         const int r = rb * 32 + lr;
         if (r < nrows) {
@@ -498,57 +555,27 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, const uint16_
                 }
         }
     }
-    __syncthreads();   // LDS is reused by the next tile of this workgroup
-    }  // persistent loop
-}
-
-// zero the round counters of the persistent kernel
-__global__ void k_zero(int *p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
 }
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
-                            void *O, int *sync_ctr, int sync_ints, hipStream_t s) {
+                            void *O, hipStream_t s) {
     static const int want = [] {
         const char *e = getenv("DHSA_ATTN_ORDER");
         return e ? atoi(e) : 8;
     }();
-    static const int persist = [] {
-        const char *e = getenv("DHSA_ATTN_PERSIST");
-        return e ? atoi(e) : 0;
-    }();
-    const int mode = attn_order(want, p.H_kv, p.G, pv.T1);
-    const int n_virtual = p.H_q * pv.T1;
-    int grid = n_virtual;
-    int *ctr = nullptr;
-    if (persist && mode > 0) {
-        // as many workgroups as the chip holds at once
-        int dev = 0, cus = 0, occ = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = (p.D == 64) ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn_mfma<64>, 256, 0)
-                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_attn_mfma<128>, 256, 0);
-        if (e != hipSuccess) return e;
-        const int resident = cus * occ / 8 * 8;
-        if (resident >= 8 && resident < n_virtual) {
-            grid = resident;
-            const int rounds = (n_virtual + grid - 1) / grid;
-            const int ints = rounds * 8 * kPhases;
-            if (persist == 1 && sync_ctr && ints <= sync_ints) {
-                ctr = sync_ctr;
-                hipLaunchKernelGGL(k_zero, dim3((ints + 255) / 256), dim3(256), 0, s, ctr, ints);
-            }
-        }
-    }
     const float c = p.scale * 1.4426950408889634f;
-#define DHSA_MFMA(DD)                                                                                       \
-    hipLaunchKernelGGL((k_attn_mfma<DD>), dim3(grid), dim3(256), 0, s, pv, (const uint16_t *)Q,             \
-                       (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, p.N_c, p.H_q, p.G,          \
-                       mode, n_virtual, ctr, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l, p.os_h,     \
-                       p.os_l)
-    if (p.D == 64) DHSA_MFMA(64); else DHSA_MFMA(128);
+#define DHSA_MFMA(DD, PAR, tile0, T)                                                                        \
+    {                                                                                                       \
+        const int mode = attn_order(want, p.H_kv, p.G, T);                                                  \
+        hipLaunchKernelGGL((k_attn_mfma<DD, PAR>), dim3(p.H_q * (T)), dim3(256), 0, s, pv, tile0, T,        \
+                           (const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O,    \
+                           p.N_c, p.H_q, p.G, mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l,      \
+                           p.os_h, p.os_l);                                                                 \
+    }
+    // tiles of more than 64 rows first (they take longest), then the key-parity tiles
+    const int T_big = pv.T_big, T_small = pv.T1 - pv.T_big;
+    if (T_big > 0) { if (p.D == 64) DHSA_MFMA(64, false, 0, T_big) else DHSA_MFMA(128, false, 0, T_big) }
+    if (T_small > 0) { if (p.D == 64) DHSA_MFMA(64, true, T_big, T_small) else DHSA_MFMA(128, true, T_big, T_small) }
 #undef DHSA_MFMA
     return hipGetLastError();
 }

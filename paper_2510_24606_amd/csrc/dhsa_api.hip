@@ -57,10 +57,11 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     // is met number at most 1 + (how many of the shortest chunks sum to < N_b),
     // plus the query chunk itself
     std::vector<int32_t> lens(p.N_c);
-    int T1 = 0;
+    int T1 = 0, T_big = 0;
     for (int k = 0; k < p.N_c; ++k) {
         lens[k] = B[k + 1] - B[k];
         T1 += (lens[k] + kRowTile - 1) / kRowTile;
+        T_big += lens[k] / kRowTile + (lens[k] % kRowTile > kRowTile / 2);
     }
     std::sort(lens.begin(), lens.end());
     int64_t acc = 0;
@@ -68,6 +69,7 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
     pl.stride = std::min(p.N_c, n + 2);
     pl.T1 = T1;
+    pl.T_big = T_big;
     pl.off_B = 16;
     pl.off_count = align_up(pl.off_B + p.N_c + 1, 4);
     pl.off_entries = align_up(pl.off_count + (int64_t)p.H_q * p.N_c, 4);
@@ -78,8 +80,7 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
 
 WsLayout ws_layout(const Prob &p) {
     WsLayout w;
-    w.off_sync = 0;                                  // kSyncInts ints: round counters of the attention kernel
-    w.off_Qc = kSyncInts / 2;
+    w.off_Qc = 0;
     w.off_Kc = align_up(w.off_Qc + (int64_t)p.H_q * p.N_c * p.D, 32);
     w.off_Sc = align_up(w.off_Kc + (int64_t)p.H_kv * p.N_c * p.D, 32);
     w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_c * p.N_c, 32);
@@ -95,6 +96,7 @@ PlanView plan_view(const PlanLayout &pl, const void *plan) {
     v.tiles = w + pl.off_tiles;
     v.stride = pl.stride;
     v.T1 = pl.T1;
+    v.T_big = pl.T_big;
     return v;
 }
 
@@ -116,12 +118,11 @@ dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, 
     return DHSA_OK;
 }
 
-dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, const void *Q, const void *K,
-                        const void *V, const void *plan, void *O, void *ws, hipStream_t s) {
+dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, const void *K, const void *V,
+                        const void *plan, void *O, hipStream_t s) {
     const PlanView pv = plan_view(pl, plan);
-    int *sync_ctr = reinterpret_cast<int *>(static_cast<double *>(ws) + wl.off_sync);
 
-    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, sync_ctr, kSyncInts, s)
+    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
                                           : launch_attn_rowwise(p, pv, Q, K, V, O, s);
     return hip_status(e);
 }
@@ -162,20 +163,16 @@ __attribute__((visibility("default"))) dhsa_status dhsa_sparse_prefill(const dhs
                                                                        const void *K_dev, const void *V_dev,
                                                                        const int32_t *B_host, const void *plan_dev,
                                                                        size_t plan_bytes, void *O_dev,
-                                                                       void *ws_dev, size_t ws_bytes,
                                                                        void *stream) {
     Prob p;
     dhsa_status st = resolve(prob, B_host, &p);
     if (st != DHSA_OK) return st;
-    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev || !ws_dev) return DHSA_ERR_NULL;
-    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) ||
-        misaligned(O_dev) || misaligned(ws_dev))
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) || misaligned(O_dev))
         return DHSA_ERR_ALIGN;
     const PlanLayout pl = plan_layout(p, B_host);
-    const WsLayout wl = ws_layout(p);
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
-    if (ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
-    return attend_impl(p, pl, wl, Q_dev, K_dev, V_dev, plan_dev, O_dev, ws_dev, static_cast<hipStream_t>(stream));
+    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, static_cast<hipStream_t>(stream));
 }
 
 __attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev,
@@ -196,7 +193,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_probl
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, s);
     if (st != DHSA_OK) return st;
-    return attend_impl(p, pl, wl, Q_dev, K_dev, V_dev, plan_dev, O_dev, ws_dev, s);
+    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
 }
 
 __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
@@ -221,7 +218,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
         hdr[4] != nb || (int64_t)hdr[6] != prob->L)
         return DHSA_ERR_PLAN;
     PlanLayout pl;
-    pl.stride = hdr[5]; pl.T1 = hdr[7];
+    pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12];
     pl.off_B = hdr[8]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
     pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;

@@ -26,6 +26,7 @@ struct Prob {
 struct PlanLayout {
     int stride;       // entries per (h, l)
     int T1;           // row tiles per head
+    int T_big;        // ... of which have more than 64 rows (listed first)
     int64_t off_B, off_count, off_entries, off_tiles, words;
 };
 
@@ -34,15 +35,14 @@ struct PlanView {
     const int32_t *B;        // [N_c + 1]
     const int32_t *count;    // [H_q][N_c]
     const int32_t *entries;  // [H_q][N_c][stride][2]
-    const int32_t *tiles;    // [T1][2]
-    int stride, T1;
+    const int32_t *tiles;    // [T1][2]: first the T_big tiles of more than 64 rows, then the rest
+    int stride, T1, T_big;
 };
 
 // Workspace layout in doubles.
 struct WsLayout {
-    int64_t off_sync, off_Qc, off_Kc, off_Sc, doubles;
+    int64_t off_Qc, off_Kc, off_Sc, doubles;
 };
-constexpr int kSyncInts = 8192;          // ints reserved at the start of the workspace for round counters
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
@@ -55,7 +55,7 @@ hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int6
 hipError_t launch_attn_rowwise(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                                void *O, hipStream_t s);
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
-                            void *O, int *sync_ctr, int sync_ints, hipStream_t s);
+                            void *O, hipStream_t s);
 
 // ---- small device helpers ----
 __device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N_c, int64_t i) {

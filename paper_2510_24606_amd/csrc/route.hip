@@ -12,12 +12,14 @@ namespace dhsa {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
-// Plan header + row-tile table.  One block; B is already in the plan.
+// Plan header + row-tile table.  One block; B is already in the plan.  Tiles
+// are the <= 128-row pieces of the chunks; the table lists first those of more
+// than 64 rows, then the others, each group ordered by row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int N_c,
                                                int N_b, int64_t L) {
-    __shared__ int s_part[256];
-    __shared__ int s_carry;
+    __shared__ int s_big[256], s_small[256];
+    __shared__ int s_carry_big, s_carry_small;
     const int tid = threadIdx.x;
     const int32_t *B = plan + pl.off_B;
     int32_t *tiles = plan + pl.off_tiles;
@@ -36,36 +38,47 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
             case 9: w = (int32_t)pl.off_count; break;
             case 10: w = (int32_t)pl.off_entries; break;
             case 11: w = (int32_t)pl.off_tiles; break;
+            case 12: w = pl.T_big; break;
             default: break;
         }
         plan[tid] = w;
     }
-    if (tid == 0) s_carry = 0;
+    if (tid == 0) { s_carry_big = 0; s_carry_small = pl.T_big; }
     __syncthreads();
     for (int base = 0; base < N_c; base += 256) {
-        int l = base + tid;
-        int b0 = 0, len = 0, nsub = 0;
+        const int l = base + tid;
+        int b0 = 0, len = 0, nfull = 0, rem = 0;
         if (l < N_c) {
             b0 = B[l];
             len = B[l + 1] - b0;
-            nsub = (len + kRowTile - 1) / kRowTile;
+            nfull = len / kRowTile;
+            rem = len % kRowTile;
         }
-        s_part[tid] = nsub;
+        const int nbig = nfull + (rem > kRowTile / 2), nsmall = (rem > 0 && rem <= kRowTile / 2);
+        s_big[tid] = nbig;
+        s_small[tid] = nsmall;
         __syncthreads();
-        // Hillis-Steele inclusive scan over the 256 slab entries
+        // Hillis-Steele inclusive scans over the 256 slab entries
         for (int off = 1; off < 256; off <<= 1) {
-            int v = (tid >= off) ? s_part[tid - off] : 0;
+            const int vb = (tid >= off) ? s_big[tid - off] : 0;
+            const int vs = (tid >= off) ? s_small[tid - off] : 0;
             __syncthreads();
-            s_part[tid] += v;
+            s_big[tid] += vb;
+            s_small[tid] += vs;
             __syncthreads();
         }
-        int start = s_carry + s_part[tid] - nsub;
-        for (int s = 0; s < nsub; ++s) {
-            tiles[2 * (start + s)] = l;
-            tiles[2 * (start + s) + 1] = b0 + s * kRowTile;
+        int at = s_carry_big + s_big[tid] - nbig;
+        for (int t = 0; t < nbig; ++t) {
+            tiles[2 * (at + t)] = l;
+            tiles[2 * (at + t) + 1] = b0 + t * kRowTile;
+        }
+        if (nsmall) {
+            at = s_carry_small + s_small[tid] - 1;
+            tiles[2 * at] = l;
+            tiles[2 * at + 1] = b0 + nfull * kRowTile;
         }
         __syncthreads();
-        if (tid == 255) s_carry += s_part[255];
+        if (tid == 255) { s_carry_big += s_big[255]; s_carry_small += s_small[255]; }
         __syncthreads();
     }
 }

@@ -92,8 +92,7 @@ def test_bad_boundaries_and_buffers(lib):
     assert lib.dhsa_route(C.byref(p), 16, 24, bp(B), 16, 1 << 30, 16, 1 << 30, None) == 9        # misaligned
     assert lib.dhsa_route(C.byref(p), 16, 16, bp(B), 16, 8, 16, 1 << 30, None) == 6              # plan too small
     assert lib.dhsa_route(C.byref(p), 16, 16, bp(B), 16, 1 << 30, 16, 8, None) == 6              # ws too small
-    assert lib.dhsa_sparse_prefill(C.byref(p), 16, 16, 16, bp(B), 16, 8, 16, 16, 1 << 30, None) == 8   # plan too small
-    assert lib.dhsa_sparse_prefill(C.byref(p), 16, 16, 16, bp(B), 16, 1 << 30, 16, 16, 8, None) == 6   # ws too small
+    assert lib.dhsa_sparse_prefill(C.byref(p), 16, 16, 16, bp(B), 16, 8, 16, None) == 8          # plan too small
     assert lib.dhsa_prefill(C.byref(p), 16, 16, None, bp(B), 16, 16, 1 << 30, 16, 1 << 30, None) == 1
     for s in range(10):
         assert len(lib.dhsa_status_string(s)) > 1

@@ -60,8 +60,14 @@ def check_plan_all_chunks(w, g):
             np.testing.assert_array_equal(e[:, 0] & ((1 << dhsa.POS_SHIFT) - 1), ks)
             np.testing.assert_array_equal(e[:, 0] >> dhsa.POS_SHIFT, pos[l, ks])
             np.testing.assert_array_equal(e[:, 1], rem[l, ks])
-    # tile table: rows of one chunk, <= 128 each, covering [0, L)
+    # tile table: rows of one chunk, <= 128 each, covering [0, L); tiles of more than 64 rows first
     t = plan["tiles"]
+    order = np.argsort(t[:, 1], kind="stable")
+    nrows_t = np.r_[t[order][1:, 1], w.L] - t[order][:, 1]
+    big = np.zeros(len(t), dtype=bool); big[order] = nrows_t > 64
+    assert big[:plan["T_big"]].all() and not big[plan["T_big"]:].any()
+    assert (np.diff(t[:plan["T_big"], 1]) > 0).all() and (np.diff(t[plan["T_big"]:, 1]) > 0).all()
+    t = t[order]
     assert t[0, 1] == 0
     ends = np.r_[t[1:, 1], w.L]
     assert ((ends - t[:, 1]) <= 128).all() and ((ends - t[:, 1]) > 0).all()
@@ -121,7 +127,7 @@ def test_small_full_parity(name, kw):
 def plans_equal(a, b):
     """Compare the defined words of two plans (slots past `count` are unspecified)."""
     pa, pb = dhsa.parse_plan(a.cpu().numpy()), dhsa.parse_plan(b.cpu().numpy())
-    for k in ("H_q", "N_c", "N_b", "stride", "L", "T1"):
+    for k in ("H_q", "N_c", "N_b", "stride", "L", "T1", "T_big"):
         if pa[k] != pb[k]:
             return False
     if not (np.array_equal(pa["B"], pb["B"]) and np.array_equal(pa["count"], pb["count"])
@@ -140,8 +146,8 @@ def test_route_then_sparse_prefill_equals_prefill_and_is_deterministic():
     plan, ws = dhsa.alloc(g1["prob"], w.B)
     dhsa.dhsa_route(g1["prob"], g1["Q"], g1["K"], w.B, plan, ws)
     O = torch.zeros_like(g1["Q"])
-    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O, ws)
-    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O, ws)   # the plan is reusable
+    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O)
+    dhsa.dhsa_sparse_prefill(g1["prob"], g1["Q"], g1["K"], g1["V"], w.B, plan, O)   # the plan is reusable
     torch.cuda.synchronize()
     assert plans_equal(plan, g1["plan"])
     assert torch.equal(O.view(torch.int16), g1["O"].view(torch.int16))
