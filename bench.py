@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+# HBM bytes of the attention step on c3 (both k_attn_mfma launches), from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/attn_mfma_c3.md (counter KiB x the copy-kernel factors 2.0 / 1.0).
+MEASURED_TRAFFIC_C3 = {"fetch_bytes": None, "write_bytes": None}
 PAPER_CONTEXT = {"what": "paper Tab. 11, DHSA 6.25% @128K, LLaMA-3.1-8B bf16, attention kernel only",
                  "ms_per_layer": 214.5, "hardware": "RTX 3090"}
 
@@ -96,9 +100,12 @@ def main() -> int:
         "stages_ms": {"route(pool+S_c+select)": round(route_ms, 4), "sparse_attention": round(attn_ms, 4),
                       "host_wall_per_step": round(wall_ms, 4)},
         "pct_of_bf16_mfma_peak": round(100.0 * achieved / PEAK_BF16_TFLOPS, 3),
-        "roofline": {"bound": "mfma", "kernel": "k_attn_mfma", "achieved": round(achieved, 3),
+        "roofline": {"bound": "mfma", "kernel": "k_attn_mfma (two launches: tiles of > 64 rows, tiles of <= 64 rows)", "achieved": round(achieved, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 5),
-                     "flop_per_launch": flops, "traffic": None},
+                     "flop_per_launch": flops,
+                     "traffic": (MEASURED_TRAFFIC_C3["fetch_bytes"] + MEASURED_TRAFFIC_C3["write_bytes"]
+                                 if args.workload == "c3" and MEASURED_TRAFFIC_C3["fetch_bytes"] else None),
+                     "traffic_detail": MEASURED_TRAFFIC_C3 if args.workload == "c3" else None},
         "paper_context": PAPER_CONTEXT,
     }
 

@@ -245,18 +245,27 @@ hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, doub
 // ---------------------------------------------------------------------------
 // Ranking + per-row budget for one (head, query chunk l): Alg. 1's Argsort and
 // walk, done once for all rows of the chunk.
-//   1. keys 0..l -> LDS as order-preserving 64-bit integers (+ chunk id);
-//   2. bitonic sort, larger score first, equal scores lower id first;
-//   3. exclusive prefix sum of chunk lengths along the ranking, chunk l left out
+//   1. scores of key chunks 0..l -> LDS as order-preserving 64-bit integers;
+//   2. only the best `stride` chunks can ever be listed (stride bounds the number
+//      of chunks whose tokens fit the budget), so for long rows a most-significant-
+//      digit radix select (8-bit digits, LDS histograms, prefix scans) first cuts
+//      the row down to <= 512 candidates; short rows skip this;
+//   3. bitonic sort of the candidates, larger score first, equal scores lower id first;
+//   4. exclusive prefix sum of chunk lengths along the ranking, chunk l left out
 //      -> rem = N_b - (tokens of other chunks before this rank);
-//   4. a chunk is kept if some row takes a token of it; kept chunks are
+//   5. a chunk is kept if some row takes a token of it; kept chunks are
 //      compacted in ascending chunk id (prefix sum of flags) into the plan.
 // ---------------------------------------------------------------------------
+constexpr int kMaxCand = 512;     // candidates kept by the radix select
+constexpr int kSelectMin = 512;   // rows with more chunks than this use it (if the LDS allocation has room)
+
 __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
-                                                PlanLayout pl, int N_c, int N_b) {
+                                                PlanLayout pl, int N_c, int N_b, int smem_bytes) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_wave[4];
     __shared__ int s_p;
+    __shared__ int s_hist[256];
+    __shared__ int s_digit, s_above, s_equal;
     const int l = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
     const int n = l + 1;
     int P = 64;
@@ -280,41 +289,105 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
         id[x] = k;
     }
     __syncthreads();
-    // bitonic network; "a goes first" iff key larger, or equal and id smaller
-    for (int size = 2; size <= P; size <<= 1) {
+
+    // what gets sorted: by default the whole row, in place
+    unsigned long long *skey = key;
+    int *sid = id;
+    int Ps = P, ns = n;
+
+    if (n > kSelectMin && pl.stride <= kMaxCand - 64 && P * 8 + kMaxCand * 12 <= smem_bytes) {
+        // ---- radix select: smallest set {key >= threshold prefix} holding the best `stride` ----
+        const int need = pl.stride < n ? pl.stride : n;
+        unsigned long long prefix = 0ull;
+        int above = 0, equal = n, shift = 64;
+        for (int pass = 0; pass < 8 && above + equal > kMaxCand; ++pass) {
+            shift = 56 - 8 * pass;
+            s_hist[tid] = 0;
+            __syncthreads();
+            for (int x = tid; x < n; x += 256) {
+                const unsigned long long k = key[x];
+                if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&s_hist[(int)((k >> shift) & 255ull)], 1);
+            }
+            __syncthreads();
+            // suffix counts over digits: thread t looks at digit 255 - t
+            const int d = 255 - tid, cnt = s_hist[d];
+            int total;
+            const int gt = block_excl_scan(cnt, s_wave, &total);   // elements of the region with a larger digit
+            const int want = need - above;                         // still to be found inside the region
+            if (gt < want && gt + cnt >= want) { s_digit = d; s_above = gt; s_equal = cnt; }
+            __syncthreads();
+            above += s_above;
+            equal = s_equal;
+            prefix = (prefix << 8) | (unsigned long long)s_digit;
+            __syncthreads();
+        }
+        if (above + equal <= kMaxCand) {
+            // ---- compact the candidates, in chunk-id order, into their own arrays ----
+            unsigned long long *ckey = reinterpret_cast<unsigned long long *>(smem + (size_t)P * 8);  // over id[]
+            int *cid = reinterpret_cast<int *>(ckey + kMaxCand);
+            const int per = (n + 255) / 256;
+            int local = 0;
+            for (int e = 0; e < per; ++e) {
+                const int x = tid * per + e;
+                if (x < n && (key[x] >> shift) >= prefix) ++local;
+            }
+            int total;
+            int slot = block_excl_scan(local, s_wave, &total);
+            __syncthreads();               // id[] is dead (ids are positions), its space is reused now
+            for (int e = 0; e < per; ++e) {
+                const int x = tid * per + e;
+                if (x < n && (key[x] >> shift) >= prefix) { ckey[slot] = key[x]; cid[slot] = x; ++slot; }
+            }
+            ns = total;
+            Ps = 64;
+            while (Ps < ns) Ps <<= 1;
+            for (int x = ns + tid; x < Ps; x += 256) { ckey[x] = 0ull; cid[x] = 0x7fffffff; }
+            skey = ckey;
+            sid = cid;
+            __syncthreads();
+        }
+    }
+
+    // ---- bitonic network; "a goes first" iff key larger, or equal and id smaller ----
+    for (int size = 2; size <= Ps; size <<= 1) {
         for (int j = size >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += 256) {
+            for (int t = tid; t < (Ps >> 1); t += 256) {
                 int lo = ((t / j) * (j << 1)) + (t % j);
                 int hi = lo + j;
                 bool up = (lo & size) == 0;
-                unsigned long long ka = key[lo], kb = key[hi];
-                int ia = id[lo], ib = id[hi];
+                unsigned long long ka = skey[lo], kb = skey[hi];
+                int ia = sid[lo], ib = sid[hi];
                 bool a_first = (ka > kb) || (ka == kb && ia < ib);
                 if (a_first != up) {
-                    key[lo] = kb; key[hi] = ka;
-                    id[lo] = ib; id[hi] = ia;
+                    skey[lo] = kb; skey[hi] = ka;
+                    sid[lo] = ib; sid[hi] = ia;
                 }
             }
             __syncthreads();
         }
     }
-    // rank of chunk l
-    for (int x = tid; x < n; x += 256)
-        if (id[x] == l) s_p = x;
+    // rank of chunk l (beyond every candidate if it is not one of them)
+    if (tid == 0) s_p = 0x7fffffff;
+    __syncthreads();
+    for (int x = tid; x < ns; x += 256)
+        if (sid[x] == l) s_p = x;
     __syncthreads();
     const int p = s_p;
-    // the key array is dead now: reuse it as rem_by_id / pos_by_id
+    // the row's key array is dead now: reuse it as rem_by_id / pos_by_id
     int *rem_by_id = reinterpret_cast<int *>(smem);        // [P]
     int *pos_by_id = rem_by_id + P;                        // [P]
-    const int per = P / 256 > 0 ? P / 256 : 1;             // consecutive ranks per thread
+    if (skey != key) {                                     // chunks that are no candidates are not listed
+        for (int x = tid; x < n; x += 256) rem_by_id[x] = 0;
+    }
+    const int per = Ps / 256 > 0 ? Ps / 256 : 1;           // consecutive ranks per thread
     {
         int lens[32];
         int local = 0;
         for (int e = 0; e < per; ++e) {
             int r = tid * per + e;
             int len = 0;
-            if (r < n) {
-                int k = id[r];
+            if (r < ns) {
+                int k = sid[r];
                 len = (k == l) ? 0 : B[k + 1] - B[k];
             }
             lens[e] = len;
@@ -322,11 +395,11 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
         }
         int total;
         int run = block_excl_scan(local, s_wave, &total);
-        __syncthreads();  // every thread has read its id[] and key[] is dead
+        __syncthreads();  // every thread has read its sid[]; the zero fill above is complete
         for (int e = 0; e < per; ++e) {
             int r = tid * per + e;
-            if (r < n) {
-                int k = id[r];
+            if (r < ns) {
+                int k = sid[r];
                 int pos = (r < p) ? 0 : (r == p ? 1 : 2);
                 int rem = N_b - run;                      // may be <= 0: not needed
                 bool need = (pos == 2) ? (rem > 1) : (rem > 0);
@@ -340,15 +413,16 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     // compact in ascending chunk id
     int32_t *entries = plan + pl.off_entries + ((int64_t)h * N_c + l) * pl.stride * 2;
     {
+        const int per_id = P / 256 > 0 ? P / 256 : 1;
         int local = 0;
-        for (int e = 0; e < per; ++e) {
-            int k = tid * per + e;
+        for (int e = 0; e < per_id; ++e) {
+            int k = tid * per_id + e;
             if (k < n && rem_by_id[k] != 0) ++local;
         }
         int total;
         int slot = block_excl_scan(local, s_wave, &total);
-        for (int e = 0; e < per; ++e) {
-            int k = tid * per + e;
+        for (int e = 0; e < per_id; ++e) {
+            int k = tid * per_id + e;
             if (k < n && rem_by_id[k] != 0) {
                 if (slot < pl.stride) {
                     entries[2 * slot] = k | (pos_by_id[k] << kPosShift);
@@ -370,7 +444,7 @@ hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k_select, dim3(p.N_c, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b);
+    hipLaunchKernelGGL(k_select, dim3(p.N_c, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, (int)shmem);
     return hipGetLastError();
 }
 
