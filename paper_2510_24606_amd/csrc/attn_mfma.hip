@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
-    float m_ref = -INFINITY, l_run = 0.f;   // m_ref: reference maximum used in the exponent (may lag the true maximum)
+    float m_ref = -INFINITY, l_run = 0.f;   // m_ref: reference used in the exponent (see DHSA_EXP)
 
     const int E = pv.count[(int64_t)h * N_c + l];
     const int32_t *ent = pv.entries + ((int64_t)h * N_c + l) * pv.stride * 2;
@@ -284,8 +284,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         }                                                                                       \
     }
 
-// mask (only tiles that hold a key some row of the tile does not take) and row maximum
-#define DHSA_MASK_MAX(n, kb, sacc, mx)                                                          \
+// mask: only tiles that hold a key some row of the tile does not take
+#define DHSA_MASK(n, kb, sacc)                                                                  \
     {                                                                                           \
         const int buf_ = (n) & 7;                                                               \
         if (sm.flags[buf_]) {                                                                   \
@@ -299,37 +299,50 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
                 sacc[q4 * 4 + 3] = ((v_i > lo_.w) & (v_i < hi_.w)) ? sacc[q4 * 4 + 3] : -INFINITY; \
             }                                                                                   \
         }                                                                                       \
+    }
+
+// row maximum of a block of S^T (the two lanes of a row exchange their halves)
+#define DHSA_ROWMAX(sacc, mx)                                                                   \
+    {                                                                                           \
         float m_ = sacc[0];                                                                     \
         _Pragma("unroll") for (int x = 1; x < 16; ++x) m_ = fmaxf(m_, sacc[x]);                 \
         mx = fmaxf(m_, __shfl_xor(m_, 32));                                                     \
     }
 
-// The reference maximum m_ref of the exponent only moves when the block maximum
-// exceeds it by more than 2^8 in probability units, so exponentials stay <= 256
-// and the accumulators are rescaled on few blocks (O / l at the end is exact
-// whatever reference was used).
-#define DHSA_RESCALE(mx)                                                                        \
-    {                                                                                           \
-        const bool move_ = mx * scale_log2e > m_ref * scale_log2e + 8.f; /* false if mx = -inf */ \
-        if (__any(move_)) {                                                                     \
-            const float m_new_ = move_ ? mx : m_ref;                                            \
-            const float alpha_ = move_ ? __builtin_amdgcn_exp2f((m_ref - m_new_) * scale_log2e) : 1.f; \
-            l_run *= alpha_;                                                                    \
-            _Pragma("unroll") for (int db = 0; db < NDB; ++db)                                  \
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha_;           \
-            m_ref = m_new_;                                                                     \
-        }                                                                                       \
-    }
-
-// P = exp2(S * c - m_ref * c), row sum, rounded to the two bf16 MFMA B operands of the block
+// P = exp2((S - m_ref) * c) with row sums, rounded to the two bf16 MFMA B operands
+// of the block.  m_ref is a REFERENCE for the exponent, not the running maximum:
+// O / l at the end is exact whatever reference was used, so it only has to keep
+// the exponentials in range.  It is set from the first block and moved up (with
+// a rescale of l and O) only when a block's exponentials grow past 2^20, which
+// the row sums reveal without a per-block maximum.  A row keeps m_ref = -inf
+// (and p = 0) until it meets its first unmasked key.
 #define DHSA_EXP(sacc, pf)                                                                      \
     {                                                                                           \
-        const float mc_ = (m_ref == -INFINITY) ? 0.f : m_ref * scale_log2e;                     \
+        float mc_ = (m_ref == -INFINITY) ? 0.f : m_ref * scale_log2e;                           \
         float psum_ = 0.f;                                                                      \
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                        \
             const float e_ = __builtin_amdgcn_exp2f(sacc[x] * scale_log2e - mc_);               \
             psum_ += e_;                                                                        \
             pf[x >> 3][x & 7] = (__bf16)e_;                                                     \
+        }                                                                                       \
+        /* too large, inf or NaN, or no reference yet (then nothing has been accumulated) */     \
+        if (__any(!(psum_ < 1048576.f) || m_ref == -INFINITY)) {                                \
+            float mx_;                                                                          \
+            DHSA_ROWMAX(sacc, mx_);                                                             \
+            const float m_new_ = fmaxf(m_ref, mx_);                                             \
+            const float alpha_ = (m_ref == -INFINITY) ? 0.f                                     \
+                                 : __builtin_amdgcn_exp2f((m_ref - m_new_) * scale_log2e);      \
+            l_run *= alpha_;                                                                    \
+            _Pragma("unroll") for (int db = 0; db < NDB; ++db)                                  \
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha_;           \
+            m_ref = m_new_;                                                                     \
+            mc_ = (m_ref == -INFINITY) ? 0.f : m_ref * scale_log2e;                             \
+            psum_ = 0.f;                                                                        \
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {                                    \
+                const float e_ = __builtin_amdgcn_exp2f(sacc[x] * scale_log2e - mc_);           \
+                psum_ += e_;                                                                    \
+                pf[x >> 3][x & 7] = (__bf16)e_;                                                 \
+            }                                                                                   \
         }                                                                                       \
         l_run += psum_;                                                                         \
     }
@@ -373,7 +386,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     }
 
         f32x16 s_a, s_b;                      // scores of two consecutive blocks (ping-pong)
-        float mx_a = -INFINITY, mx_b = -INFINITY;
         int toggle = kTile;                   // +tile, -tile, ...: k_off / v_base_* follow the tile buffers
         if (wave < ntiles) DHSA_MAKE_META(wave);   // key lists of tiles 0..3
         __syncthreads();
@@ -388,7 +400,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         __syncthreads();
         if (wave_live) {
             DHSA_QK(0, s_a);
-            DHSA_MASK_MAX(0, 0, s_a, mx_a);
+            DHSA_MASK(0, 0, s_a);
+            if (e0 == 0) DHSA_ROWMAX(s_a, m_ref);          // first block of the tile: reference = its row maxima
         }
         __syncthreads();                      // the lower half of K(0) may be overwritten from here on
 
@@ -402,18 +415,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
             if (wave_live) {
                 bf16x8 pf[2];
-                DHSA_RESCALE(mx_a);
                 DHSA_QK(32 * D, s_b);                      // block 1 of tile n
                 DHSA_EXP(s_a, pf);
                 DHSA_PV(0, pf);
-                DHSA_MASK_MAX(n, 1, s_b, mx_b);
-                DHSA_RESCALE(mx_b);
+                DHSA_MASK(n, 1, s_b);
 #pragma unroll
                 for (int s = 0; s < NS; ++s) k_off[s] += toggle;   // now the K buffer of tile n+1
                 DHSA_QK(0, s_a);                           // block 0 of tile n+1
                 DHSA_EXP(s_b, pf);
                 DHSA_PV(1, pf);
-                DHSA_MASK_MAX(n + 1, 0, s_a, mx_a);
+                DHSA_MASK(n + 1, 0, s_a);
                 v_base_e += toggle;                        // now the V buffer of tile n+1
                 v_base_o += toggle;
                 toggle = -toggle;
@@ -424,12 +435,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         // ---- last tile of the batch: nothing left to load or to score ahead ----
         if (wave_live) {
             bf16x8 pf[2];
-            DHSA_RESCALE(mx_a);
             DHSA_QK(32 * D, s_b);
             DHSA_EXP(s_a, pf);
             DHSA_PV(0, pf);
-            DHSA_MASK_MAX(n, 1, s_b, mx_b);
-            DHSA_RESCALE(mx_b);
+            DHSA_MASK(n, 1, s_b);
             DHSA_EXP(s_b, pf);
             DHSA_PV(1, pf);
         }
@@ -451,7 +460,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         __syncthreads();
         if (wave_live) {
             DHSA_QK(0, s_a);
-            DHSA_MASK_MAX(0, kbw, s_a, mx_a);
+            DHSA_MASK(0, kbw, s_a);
+            if (e0 == 0) DHSA_ROWMAX(s_a, m_ref);          // first block of this wave: reference = its row maxima
 #pragma unroll
             for (int s = 0; s < NS; ++s) k_off[s] += kTile;   // K offsets run one tile ahead of V offsets
         }
@@ -466,13 +476,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
             if (wave_live) {
                 bf16x8 pf[2];
-                DHSA_RESCALE(mx_a);
                 DHSA_QK(0, s_b);
                 DHSA_EXP(s_a, pf);
                 DHSA_PV(0, pf);
-                DHSA_MASK_MAX(n + 1, kbw, s_b, mx_b);
+                DHSA_MASK(n + 1, kbw, s_b);
                 s_a = s_b;
-                mx_a = mx_b;
 #pragma unroll
                 for (int s = 0; s < NS; ++s) k_off[s] -= toggle;
                 v_base_e += toggle;
@@ -484,7 +492,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         }
         if (wave_live) {                          // last tile of the batch
             bf16x8 pf[2];
-            DHSA_RESCALE(mx_a);
             DHSA_EXP(s_a, pf);
             DHSA_PV(0, pf);
         }
@@ -505,8 +512,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
 #undef DHSA_LOAD_K_HI
 #undef DHSA_LOAD_V
 #undef DHSA_QK
-#undef DHSA_MASK_MAX
-#undef DHSA_RESCALE
+#undef DHSA_MASK
+#undef DHSA_ROWMAX
 #undef DHSA_EXP
 #undef DHSA_PV
 #undef DHSA_SCHED

@@ -172,6 +172,25 @@ def test_strided_inputs_and_explicit_scale():
     check_outputs(w, g, rows, O_ref)
 
 
+def test_peaky_softmax_moves_the_exponent_reference():
+    """Logits spread over +-50 (scale 1 instead of 1/sqrt(d)): the probabilities of
+    later key blocks exceed those of the first block by far more than 2^20, so the
+    kernel has to move its exponent reference and rescale (several times per row)."""
+    for name, kw in (("c2", dict(L=6000, H_q=8, H_kv=2, N_b=384)), ("c3", dict(L=4096, H_q=4, H_kv=2, N_b=512))):
+        w = dhsa_inputs.make(name, **kw)
+        g = run_gpu(w, scale=1.0)
+        rows = np.arange(w.L, dtype=np.int64)
+        O_ref, _, _ = oracle.prefill_rows(w.f32("Q"), w.f32("K"), w.f32("V"), w.B, w.N_b, rows, scale=1.0)
+        got = g["O"].float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        err = np.abs(got - O_ref).max()
+        # near one-hot rows return single value vectors, |O| up to ~4.5 here: rounding O to bf16
+        # costs up to |O| * 2^-8 (half an ulp), rounding the probabilities another |O| * 2^-9
+        tol = np.abs(O_ref).max() * (2.0 ** -8 + 2.0 ** -9) * 1.05
+        print(f"   {name}: peaky softmax max |O - oracle| = {err:.3e} (bound {tol:.3e})", flush=True)
+        assert err <= tol
+
+
 FULL = ["c2", "c3", "c4", "c5"]
 
 
