@@ -25,8 +25,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 # HBM bytes of the attention step on c3 (both k_attn_mfma launches), from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/attn_mfma_c3.md (counter KiB x the copy-kernel factors 2.0 / 1.0).
-MEASURED_TRAFFIC_C3 = {"fetch_bytes": None, "write_bytes": None}
+# profiles/attn_mfma_c3_counters.md (counter KiB x the copy-kernel factors 2.0 / 1.0 of
+# profiles/counter_calibration.md).  The K/V gather asks the L2 for 220 GB; 41 % of it hits.
+MEASURED_TRAFFIC_C3 = {"fetch_bytes": 1.32e11, "write_bytes": 1.074e9}
 PAPER_CONTEXT = {"what": "paper Tab. 11, DHSA 6.25% @128K, LLaMA-3.1-8B bf16, attention kernel only",
                  "ms_per_layer": 214.5, "hardware": "RTX 3090"}
 
