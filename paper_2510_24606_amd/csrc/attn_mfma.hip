@@ -74,7 +74,9 @@ struct AttnSmem {
     static constexpr int kTile = kKT * D;            // elements of one K (or V) tile, rows unpadded
     alignas(1024) uint16_t K[2 * kTile];
     alignas(1024) uint16_t V[2 * kTile];
-    alignas(16) unsigned key_koff[8][kKT];   // byte offset of the key's row in K / V of this kv-head
+    // byte offset of each key's row in K / V of this kv-head, stored in the order the
+    // loading lanes want them (see off_slot): the rows one lane fetches are adjacent
+    alignas(16) unsigned key_koff[8][kKT];
     alignas(16) unsigned key_voff[8][kKT];
     alignas(16) int key_lo[8][kKT];
     alignas(16) int key_hi[8][kKT];
@@ -162,14 +164,20 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     const char *Vg8 = reinterpret_cast<const char *>(V + (int64_t)g * vs_h);
     const unsigned k_row_bytes = (unsigned)ks_l * 2u, v_row_bytes = (unsigned)vs_l * 2u;
 
-    // Q fragments: B operand of S^T = K Q^T; lane holds row lr, d = 16 s + 8 g2 .. + 7
+    // Q fragments: B operand of S^T = K Q^T; lane holds row lr, d = 16 s + 8 g2 .. + 7.
+    // Padding rows (past the end of the tile; never stored) get q = 0 and, through a
+    // huge exponent reference, p = 0: all-zero operand columns keep the matrix unit's
+    // switching activity, and with it the power drawn for rows that do not exist, low.
     bf16x8 qf[NS];
+    const bool pad_row = rb * 32 + lr >= nrows;
     {
-        int r = rb * 32 + lr;
-        if (r >= nrows) r = nrows - 1;  // padding rows read a valid row; never stored
+        const int r = pad_row ? nrows - 1 : rb * 32 + lr;
         const uint16_t *qp = Q + (int64_t)h * qs_h + (int64_t)(row0 + r) * qs_l + 8 * g2;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+        for (int s = 0; s < NS; ++s) {
+            qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+            if (pad_row) qf[s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
     }
 
     f32x16 oacc[NDB];
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
-    float m_ref = -INFINITY, l_run = 0.f;   // m_ref: reference used in the exponent (see DHSA_EXP)
+    float m_ref = pad_row ? 1e30f : -INFINITY, l_run = 0.f;   // m_ref: reference used in the exponent (see DHSA_EXP)
 
     const int E = pv.count[(int64_t)h * N_c + l];
     const int32_t *ent = pv.entries + ((int64_t)h * N_c + l) * pv.stride * 2;
@@ -189,14 +197,19 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     constexpr int RPW = 64 / OPR;                                     // rows per window
     const int ld_row0 = wave * RPW + lane / OPR;
     const unsigned ld_piece_bytes = 16u * ((lane % OPR) ^ piece_swizzle(ld_row0, OPR));
+    // the rows one lane fetches for a tile are ld_row0 + c RSTR, c = 0 .. KPT-1; the offset of
+    // key row r sits in slot (r % RSTR) KPT + r / RSTR of the tile's offset table
+    constexpr int RSTR = 4 * RPW;
+    const int off_slot_wr = (lane % RSTR) * KPT + lane / RSTR;   // slot of key `lane` (writer side)
+    const int off_slot_rd = ld_row0 * KPT;                        // first slot of this lane's rows
     const unsigned lds_K = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.K;
     const unsigned lds_V = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.V;
-    // operand fragments (element offsets inside a tile)
+    // operand fragments (byte offsets inside the K / V buffers)
     //   K: row kb*32 + lr, logical piece 2 s + g2
     const int k_sw = piece_swizzle(lr, OPR);
     int k_off[NS];   // points into the K buffer of the current tile; moved once per tile
 #pragma unroll
-    for (int s = 0; s < NS; ++s) k_off[s] = (kbw * 32 + lr) * D + 8 * ((2 * s + g2) ^ k_sw);
+    for (int s = 0; s < NS; ++s) k_off[s] = 2 * ((kbw * 32 + lr) * D + 8 * ((2 * s + g2) ^ k_sw));
     // Transpose-read source of this lane: row 8 half + 4 g2 + c of a 16-row group,
     // logical piece P = 4 db + 2 dh + (r >> 1), physical piece P ^ swizzle(row).  The
     // swizzle's bits 2-3 are (c >> 1) and half, so the physical piece is
@@ -206,8 +219,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     const int tr_c = (lane & 15) >> 2, tr_r = lane & 3, tr_dh = (lane >> 4) & 1;
     const int tr_low2 = ((tr_r >> 1) ^ g2) | ((tr_dh ^ (tr_c & 1)) << 1);
     const int tr_l0 = (4 * g2 + tr_c) * D + 8 * tr_low2 + 4 * (tr_r & 1);
-    int v_base_e = kbw * 32 * D + tr_l0 + 32 * (tr_c >> 1);   // moved once per tile
-    int v_base_o = kbw * 32 * D + tr_l0 - 32 * (tr_c >> 1);
+    int v_base_e = 2 * (kbw * 32 * D + tr_l0 + 32 * (tr_c >> 1));   // moved once per tile
+    int v_base_o = 2 * (kbw * 32 * D + tr_l0 - 32 * (tr_c >> 1));
+    const char *const smK8 = reinterpret_cast<const char *>(sm.K);
+    const char *const smV8 = reinterpret_cast<const char *>(sm.V);
 
     for (int e0 = 0; e0 < E; e0 += kSegB) {
         // ---- segment table of this batch of plan entries ----
@@ -252,26 +267,30 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         int hi_ = (pos_ == 2) ? sm.seg_rem[seg_] - t_ : kIntMax;                                \
         if (pad_) { lo_ = kIntMax; hi_ = kIntMax; }                                             \
         const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
-        sm.key_koff[buf_][lane] = j_ * k_row_bytes;                                             \
-        sm.key_voff[buf_][lane] = j_ * v_row_bytes;                                             \
+        sm.key_koff[buf_][off_slot_wr] = j_ * k_row_bytes;                                      \
+        sm.key_voff[buf_][off_slot_wr] = j_ * v_row_bytes;                                      \
         sm.key_lo[buf_][lane] = lo_;                                                            \
         sm.key_hi[buf_][lane] = hi_;                                                            \
         const unsigned long long any_ = __ballot((lo_ >= v_lo) || (hi_ <= v_hi));               \
         if (lane == 0) sm.flags[buf_] = any_ != 0ull;                                           \
     }
 
-// issue the global -> LDS loads of windows c0..c1-1 of the K (or V) rows of tile n
-#define DHSA_GLOAD(lds_base, off_tab, base8, n, c0, c1)                                         \
+// fetch this lane's row offsets of tile n into registers (windows c0..c1-1)
+#define DHSA_OFFS(dst, off_tab, n, c0, c1)                                                      \
+    _Pragma("unroll") for (int c = c0; c < c1; ++c) dst[c] = sm.off_tab[(n) & 7][off_slot_rd + c];
+// issue the global -> LDS loads of windows c0..c1-1 of the K (or V) rows of tile n,
+// row offsets taken from registers
+#define DHSA_GLOAD(lds_base, offs, base8, n, c0, c1)                                            \
     {                                                                                           \
-        const int buf_ = (n) & 7;                                                               \
         const unsigned dst_ = lds_base + (((n) & 1) * kTile + wave_u * 512) * 2;                \
         _Pragma("unroll") for (int c = c0; c < c1; ++c)                                         \
-            load16_to_lds(base8, sm.off_tab[buf_][ld_row0 + c * 4 * RPW] + ld_piece_bytes,      \
-                          dst_ + c * 4096);                                                     \
+            load16_to_lds(base8, offs[c] + ld_piece_bytes, dst_ + c * 4096);                    \
     }
-#define DHSA_LOAD_K_LO(n) DHSA_GLOAD(lds_K, key_koff, Kg8, n, 0, KPT / 2)      /* keys 0..31  */
-#define DHSA_LOAD_K_HI(n) DHSA_GLOAD(lds_K, key_koff, Kg8, n, KPT / 2, KPT)    /* keys 32..63 */
-#define DHSA_LOAD_V(n) DHSA_GLOAD(lds_V, key_voff, Vg8, n, 0, KPT)
+#define DHSA_LOAD_K_LO(n) DHSA_GLOAD(lds_K, ko_lo, Kg8, n, 0, KPT / 2)      /* keys 0..31  */
+#define DHSA_LOAD_K_HI(n) DHSA_GLOAD(lds_K, ko_hi, Kg8, n, KPT / 2, KPT)    /* keys 32..63 */
+#define DHSA_LOAD_V(n) DHSA_GLOAD(lds_V, vo, Vg8, n, 0, KPT)
+#define DHSA_LOAD_V_LO(n) DHSA_GLOAD(lds_V, vo, Vg8, n, 0, KPT / 2)
+#define DHSA_LOAD_V_HI(n) DHSA_GLOAD(lds_V, vo, Vg8, n, KPT / 2, KPT)
 
 // S^T of one 32-key block whose K rows start at element offset kb_off of the
 // buffer k_off points into: keys = MFMA rows, this lane's query row = column lr
@@ -279,16 +298,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     {                                                                                           \
         _Pragma("unroll") for (int x = 0; x < 16; ++x) sacc[x] = 0.f;                           \
         _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                        \
-            const bf16x8 kf_ = *reinterpret_cast<const bf16x8 *>(&sm.K[k_off[s] + (kb_off)]);   \
+            const bf16x8 kf_ = *reinterpret_cast<const bf16x8 *>(smK8 + k_off[s] + 2 * (kb_off)); \
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf_, qf[s], sacc, 0, 0, 0);          \
         }                                                                                       \
     }
 
 // mask: only tiles that hold a key some row of the tile does not take
-#define DHSA_MASK(n, kb, sacc)                                                                  \
+#define DHSA_MASK(n, kb, sacc, flag)                                                            \
     {                                                                                           \
         const int buf_ = (n) & 7;                                                               \
-        if (sm.flags[buf_]) {                                                                   \
+        if (flag) {                                                                             \
             _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) {                                  \
                 const int key_ = (kb) * 32 + q4 * 8 + g2 * 4;                                   \
                 const int4 lo_ = *reinterpret_cast<const int4 *>(&sm.key_lo[buf_][key_]);       \
@@ -356,8 +375,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
                 union { s16x4 h[2]; bf16x8 v; } vf_;                                            \
                 _Pragma("unroll") for (int half = 0; half < 2; ++half) {                        \
                     const int x2_ = (OPR == 16) ? (db ^ (2 * half)) : db;                       \
-                    const uint16_t *vp_ = &sm.V[((x2_ & 1) ? v_base_o : v_base_e) +             \
-                                                ((kb) * 32 + 16 * kk + 8 * half) * D + 32 * x2_]; \
+                    const char *vp_ = smV8 + ((x2_ & 1) ? v_base_o : v_base_e) +                \
+                                      2 * (((kb) * 32 + 16 * kk + 8 * half) * D + 32 * x2_);    \
                     vf_.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                      \
                         (s16x4 __attribute__((address_space(3))) *)vp_);                        \
                 }                                                                               \
@@ -386,22 +405,30 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     }
 
         f32x16 s_a, s_b;                      // scores of two consecutive blocks (ping-pong)
-        int toggle = kTile;                   // +tile, -tile, ...: k_off / v_base_* follow the tile buffers
+        int toggle = 2 * kTile;               // +tile, -tile, ... (bytes): k_off / v_base_* follow the tile buffers
+        unsigned ko_lo[KPT], ko_hi[KPT], vo[KPT];   // row offsets of the loads this lane issues next
         if (wave < ntiles) DHSA_MAKE_META(wave);   // key lists of tiles 0..3
         __syncthreads();
         if constexpr (!PAR) {
         // ================= tiles of more than 64 rows =================
         // ---- prologue: K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
+        DHSA_OFFS(ko_lo, key_koff, 0, 0, KPT / 2);
+        DHSA_OFFS(ko_hi, key_koff, 0, KPT / 2, KPT);
+        DHSA_OFFS(vo, key_voff, 0, 0, KPT);
         DHSA_LOAD_K_LO(0);
         DHSA_LOAD_K_HI(0);
         DHSA_LOAD_V(0);
-        if (ntiles > 1) DHSA_LOAD_K_LO(1);
+        if (ntiles > 1) {
+            DHSA_OFFS(ko_lo, key_koff, 1, 0, KPT / 2);
+            DHSA_LOAD_K_LO(1);
+        }
+        int fl_cur = __builtin_amdgcn_readfirstlane(sm.flags[0]);   // does tile n need the mask?
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's pieces are in LDS
         __syncthreads();
         if (wave_live) {
             DHSA_QK(0, s_a);
-            DHSA_MASK(0, 0, s_a);
-            if (e0 == 0) DHSA_ROWMAX(s_a, m_ref);          // first block of the tile: reference = its row maxima
+            DHSA_MASK(0, 0, s_a, fl_cur);
+            if (e0 == 0) { float mx0; DHSA_ROWMAX(s_a, mx0); m_ref = fmaxf(m_ref, mx0); }   // reference = row maxima of the first block
         }
         __syncthreads();                      // the lower half of K(0) may be overwritten from here on
 
@@ -409,26 +436,41 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         // matrix unit computes the scores of the next block while the vector unit exponentiates ----
         int n = 0;
         for (; n + 1 < ntiles; ++n) {
-            DHSA_LOAD_K_HI(n + 1);                     // over K(n-1), upper half
-            DHSA_LOAD_V(n + 1);                        // over V(n-1)
-            if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2); // over K(n), lower half
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
+            // The loads of this iteration (upper half of K(n+1) over K(n-1), V(n+1) over
+            // V(n-1), lower half of K(n+2) over K(n)) are spread over the block steps so
+            // that the four waves do not hand them to the memory pipeline in one burst;
+            // their row offsets and the mask flag of tile n+1 are fetched up front, so
+            // that no load has to wait for LDS in the middle of the block steps.
+            DHSA_OFFS(ko_hi, key_koff, n + 1, KPT / 2, KPT);
+            DHSA_OFFS(vo, key_voff, n + 1, 0, KPT);
+            DHSA_OFFS(ko_lo, key_koff, n + 2, 0, KPT / 2);
+            const int fl_next = __builtin_amdgcn_readfirstlane(sm.flags[(n + 1) & 7]);
             if (wave_live) {
                 bf16x8 pf[2];
+                DHSA_LOAD_K_HI(n + 1);
                 DHSA_QK(32 * D, s_b);                      // block 1 of tile n
                 DHSA_EXP(s_a, pf);
+                DHSA_LOAD_V_LO(n + 1);
                 DHSA_PV(0, pf);
-                DHSA_MASK(n, 1, s_b);
+                DHSA_MASK(n, 1, s_b, fl_cur);
 #pragma unroll
                 for (int s = 0; s < NS; ++s) k_off[s] += toggle;   // now the K buffer of tile n+1
+                DHSA_LOAD_V_HI(n + 1);
                 DHSA_QK(0, s_a);                           // block 0 of tile n+1
                 DHSA_EXP(s_b, pf);
+                if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2);
                 DHSA_PV(1, pf);
-                DHSA_MASK(n + 1, 0, s_a);
+                DHSA_MASK(n + 1, 0, s_a, fl_next);
                 v_base_e += toggle;                        // now the V buffer of tile n+1
                 v_base_o += toggle;
                 toggle = -toggle;
+            } else {
+                DHSA_LOAD_K_HI(n + 1);
+                DHSA_LOAD_V(n + 1);
+                if (n + 2 < ntiles) DHSA_LOAD_K_LO(n + 2);
             }
+            fl_cur = fl_next;
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the pieces this wave requested have landed
             __syncthreads();
         }
@@ -438,32 +480,41 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             DHSA_QK(32 * D, s_b);
             DHSA_EXP(s_a, pf);
             DHSA_PV(0, pf);
-            DHSA_MASK(n, 1, s_b);
+            DHSA_MASK(n, 1, s_b, fl_cur);
             DHSA_EXP(s_b, pf);
             DHSA_PV(1, pf);
         }
         __syncthreads();                          // LDS is reused by the next batch
         if (wave_live && !(ntiles & 1)) {         // leave the offsets at buffer 0 for the next batch
 #pragma unroll
-            for (int s = 0; s < NS; ++s) k_off[s] -= kTile;
-            v_base_e -= kTile;
-            v_base_o -= kTile;
+            for (int s = 0; s < NS; ++s) k_off[s] -= 2 * kTile;
+            v_base_e -= 2 * kTile;
+            v_base_o -= 2 * kTile;
         }
         } else {
         // ================= tiles of at most 64 rows: one 32-key block per wave and tile =================
         // ---- prologue: K(0), V(0), K(1) in LDS; S(0, own block) ----
+        DHSA_OFFS(ko_lo, key_koff, 0, 0, KPT / 2);
+        DHSA_OFFS(ko_hi, key_koff, 0, KPT / 2, KPT);
+        DHSA_OFFS(vo, key_voff, 0, 0, KPT);
         DHSA_LOAD_K_LO(0);
         DHSA_LOAD_K_HI(0);
         DHSA_LOAD_V(0);
-        if (ntiles > 1) { DHSA_LOAD_K_LO(1); DHSA_LOAD_K_HI(1); }
+        if (ntiles > 1) {
+            DHSA_OFFS(ko_lo, key_koff, 1, 0, KPT / 2);
+            DHSA_OFFS(ko_hi, key_koff, 1, KPT / 2, KPT);
+            DHSA_LOAD_K_LO(1);
+            DHSA_LOAD_K_HI(1);
+        }
+        const int fl_0 = __builtin_amdgcn_readfirstlane(sm.flags[0]);
         __builtin_amdgcn_s_waitcnt(0x0f70);
         __syncthreads();
         if (wave_live) {
             DHSA_QK(0, s_a);
-            DHSA_MASK(0, kbw, s_a);
-            if (e0 == 0) DHSA_ROWMAX(s_a, m_ref);          // first block of this wave: reference = its row maxima
+            DHSA_MASK(0, kbw, s_a, fl_0);
+            if (e0 == 0) { float mx0; DHSA_ROWMAX(s_a, mx0); m_ref = fmaxf(m_ref, mx0); }   // reference = row maxima of this wave's first block
 #pragma unroll
-            for (int s = 0; s < NS; ++s) k_off[s] += kTile;   // K offsets run one tile ahead of V offsets
+            for (int s = 0; s < NS; ++s) k_off[s] += 2 * kTile;   // K offsets run one tile ahead of V offsets
         }
         __syncthreads();                      // K(0) may be overwritten from here on
 
@@ -471,6 +522,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         // while the matrix unit computes the scores of its block of tile n+1 (into s_b) ----
         int n = 0;
         for (; n + 1 < ntiles; ++n) {
+            DHSA_OFFS(ko_lo, key_koff, n + 2, 0, KPT / 2);
+            DHSA_OFFS(ko_hi, key_koff, n + 2, KPT / 2, KPT);
+            DHSA_OFFS(vo, key_voff, n + 1, 0, KPT);
+            const int fl_next = __builtin_amdgcn_readfirstlane(sm.flags[(n + 1) & 7]);
             if (n + 2 < ntiles) { DHSA_LOAD_K_LO(n + 2); DHSA_LOAD_K_HI(n + 2); }   // over K(n)
             DHSA_LOAD_V(n + 1);                                                    // over V(n-1)
             if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
@@ -479,7 +534,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
                 DHSA_QK(0, s_b);
                 DHSA_EXP(s_a, pf);
                 DHSA_PV(0, pf);
-                DHSA_MASK(n + 1, kbw, s_b);
+                DHSA_MASK(n + 1, kbw, s_b, fl_next);
                 s_a = s_b;
 #pragma unroll
                 for (int s = 0; s < NS; ++s) k_off[s] -= toggle;
@@ -499,18 +554,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         if (wave_live) {                          // leave the offsets at buffer 0 for the next batch
             if (ntiles & 1) {
 #pragma unroll
-                for (int s = 0; s < NS; ++s) k_off[s] -= kTile;
+                for (int s = 0; s < NS; ++s) k_off[s] -= 2 * kTile;
             } else {
-                v_base_e -= kTile;
-                v_base_o -= kTile;
+                v_base_e -= 2 * kTile;
+                v_base_o -= 2 * kTile;
             }
         }
         }
 #undef DHSA_MAKE_META
+#undef DHSA_OFFS
 #undef DHSA_GLOAD
 #undef DHSA_LOAD_K_LO
 #undef DHSA_LOAD_K_HI
 #undef DHSA_LOAD_V
+#undef DHSA_LOAD_V_LO
+#undef DHSA_LOAD_V_HI
 #undef DHSA_QK
 #undef DHSA_MASK
 #undef DHSA_ROWMAX
