@@ -109,6 +109,14 @@ def main() -> int:
                      "traffic_detail": MEASURED_TRAFFIC_C3 if args.workload == "c3" else None},
         "paper_context": PAPER_CONTEXT,
     }
+    # what the matrix unit alone sustains on this chip (same instruction as the attention kernel):
+    # with operands that never change, and with random operands (the chip then clocks down to stay
+    # inside its power limit, as it does on real attention data)
+    tf_c, mhz_c = dhsa.dhsa_mfma_probe(False)
+    tf_r, mhz_r = dhsa.dhsa_mfma_probe(True)
+    out["mfma_microkernel"] = {"constant_operands_tflops": round(tf_c, 1), "constant_operands_shader_mhz": round(mhz_c),
+                               "random_operands_tflops": round(tf_r, 1), "random_operands_shader_mhz": round(mhz_r),
+                               "attention_vs_random_operand_rate": round(achieved / tf_r, 4)}
 
     if not args.no_cpu_baseline:
         import oracle

@@ -150,6 +150,21 @@ dhsa_status dhsa_plan_expand_rows(const dhsa_problem *prob, const void *plan_dev
 dhsa_status dhsa_debug_routing(const dhsa_problem *prob, const int32_t *B_host, const void *ws_dev,
                                size_t ws_bytes, double *Qc_dev, double *Kc_dev, double *Sc_dev, void *stream);
 
+/* Measurement aid (not a step of the method): the sustained rate of the bf16
+ * matrix instruction the attention kernel (Alg. 3's QK^T and PV products) is
+ * built on, alone in a loop on every CU, for `iters` x 16 instructions per
+ * wave.  random_operands = 0: operands never change (the chip reaches its
+ * published rate); 1: eight rotating sets of random operands (the chip lowers
+ * its clock to stay inside its power limit, as it does under real attention
+ * data).  scratch_dev: device memory of at least dhsa_mfma_probe_scratch_bytes()
+ * bytes, contents overwritten.  Results go to HOST doubles: TFLOP/s over the
+ * whole chip and (may be NULL) the average shader clock of one wave in MHz.
+ * Unlike the other entry points this one BLOCKS until the kernel has run (it
+ * times it with two events on `stream`).  iters in [1, 2^22]. */
+dhsa_status dhsa_mfma_probe(int random_operands, int iters, void *scratch_dev, size_t scratch_bytes,
+                            double *tflops_host, double *shader_mhz_host, void *stream);
+size_t dhsa_mfma_probe_scratch_bytes(void);
+
 const char *dhsa_status_string(dhsa_status s);
 int dhsa_version(void);
 

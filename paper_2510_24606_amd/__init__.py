@@ -21,7 +21,8 @@ PLAN_MAGIC = 0x41534844
 POS_SHIFT = 28
 
 EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse_prefill", "dhsa_prefill",
-           "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_status_string", "dhsa_version"]
+           "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
+           "dhsa_status_string", "dhsa_version"]
 
 
 class dhsa_problem(C.Structure):
@@ -63,6 +64,9 @@ def lib() -> C.CDLL:
         l.dhsa_plan_expand_rows.restype = C.c_int
         l.dhsa_debug_routing.argtypes = [P, i32p, vp, C.c_size_t, vp, vp, vp, vp]
         l.dhsa_debug_routing.restype = C.c_int
+        l.dhsa_mfma_probe.argtypes = [C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+        l.dhsa_mfma_probe.restype = C.c_int
+        l.dhsa_mfma_probe_scratch_bytes.argtypes = []; l.dhsa_mfma_probe_scratch_bytes.restype = C.c_size_t
         l.dhsa_status_string.argtypes = [C.c_int]; l.dhsa_status_string.restype = C.c_char_p
         l.dhsa_version.argtypes = []; l.dhsa_version.restype = C.c_int
         _lib = l
@@ -171,6 +175,18 @@ def dhsa_debug_routing(prob, B, ws, want_Sc: bool = True):
     _check(lib().dhsa_debug_routing(C.byref(prob), _bp(B), ws.data_ptr(), ws.numel(), Qc.data_ptr(), Kc.data_ptr(),
                                     Sc.data_ptr() if want_Sc else None, _stream()))
     return Qc, Kc, Sc
+
+
+def dhsa_mfma_probe(random_operands: bool, iters: int = 100000):
+    """(TFLOP/s, shader MHz) of the bf16 MFMA alone on the whole chip; blocks until measured."""
+    import torch
+    L = lib()
+    n = int(L.dhsa_mfma_probe_scratch_bytes())
+    scratch = torch.empty(n, dtype=torch.uint8, device="cuda")
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    _check(L.dhsa_mfma_probe(int(bool(random_operands)), int(iters), scratch.data_ptr(), n, C.byref(tf), C.byref(mhz),
+                             _stream()))
+    return tf.value, mhz.value
 
 
 def dhsa_version() -> int:

@@ -98,6 +98,19 @@ def test_bad_boundaries_and_buffers(lib):
         assert len(lib.dhsa_status_string(s)) > 1
 
 
+def test_mfma_probe_rejects_bad_arguments_on_the_host(lib):
+    import ctypes as C
+    tf = C.c_double(0.0)
+    need = lib.dhsa_mfma_probe_scratch_bytes()
+    assert need >= 512 * 256 * 4
+    fake = C.c_void_p(256)   # never dereferenced: every call below fails validation first (1 NULL, 2 SHAPE, 6 WORKSPACE)
+    assert lib.dhsa_mfma_probe(0, 100, None, need, C.byref(tf), None, None) == 1
+    assert lib.dhsa_mfma_probe(0, 100, fake, need, None, None, None) == 1
+    assert lib.dhsa_mfma_probe(0, 0, fake, need, C.byref(tf), None, None) == 2
+    assert lib.dhsa_mfma_probe(0, 1 << 23, fake, need, C.byref(tf), None, None) == 2
+    assert lib.dhsa_mfma_probe(0, 100, fake, need - 1, C.byref(tf), None, None) == 6
+
+
 def test_no_oracle_in_the_product_path():
     """The product package must not import, load or call the oracle."""
     pkg = os.path.join(ROOT, "paper_2510_24606_amd")

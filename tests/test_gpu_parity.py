@@ -210,3 +210,14 @@ def test_full_size_sampled_parity(name):
     err = check_outputs(w, g, rows, O_ref)
     print(f"   mask exact (sample of {len(rows)} rows + plan of all chunks); near-tie groups (<=1e-5): {near}; "
           f"max |O - oracle| = {err:.3e}", flush=True)
+
+
+@pytest.mark.gpu
+def test_mfma_probe_reports_plausible_rates():
+    """The matrix-unit probe: constant operands reach the neighbourhood of the published 2.5 PFLOP/s,
+    random operands (power-limited) stay below that and above a third of it; clocks are sane."""
+    tf_c, mhz_c = dhsa.dhsa_mfma_probe(False, 50000)
+    tf_r, mhz_r = dhsa.dhsa_mfma_probe(True, 50000)
+    assert 1200.0 < tf_c < 2600.0, tf_c
+    assert 800.0 < tf_r <= tf_c * 1.02, (tf_r, tf_c)
+    assert 500.0 < mhz_r < 2600.0 and 500.0 < mhz_c < 2600.0, (mhz_c, mhz_r)
