@@ -191,3 +191,91 @@ def plan_head(Qc_h, Kc_g, B, N_b: int):
                                      _p(rem, C.c_int32), _p(pos, C.c_int8), _p(gap, C.c_double))
     assert rc == 0
     return rem, pos, gap
+
+
+# ---- Alg. 1 as printed: fixed row blocks ----
+
+def pool_blocks(X: np.ndarray, B_r: int) -> np.ndarray:
+    """Row-block query representations sqrt(B_r) * AvgPool of X [H, L, D] -> [H, N_r, D] (fp64)."""
+    X = _f32(X)
+    H, L, D = X.shape
+    N_r = (L + B_r - 1) // B_r
+    out = np.empty((H, N_r, D), dtype=np.float64)
+    rc = lib().dhsa_oracle_pool_blocks(_p(X, C.c_float), H, C.c_int64(L), D, B_r, _p(out, C.c_double))
+    assert rc == 0
+    return out
+
+
+def select_block(q_i, Kc_g, B, q_max: int, N_b: int) -> np.ndarray:
+    """Alg. 1 for one row block: scores against every key chunk, stable ranking, walk with q_max."""
+    q_i = _f64(q_i); Kc_g = _f64(Kc_g); B = _i32(B)
+    N_c, D = Kc_g.shape
+    out = np.empty(N_b, dtype=np.int32)
+    n = lib().dhsa_oracle_select_block(_p(q_i, C.c_double), _p(Kc_g, C.c_double), _p(B, C.c_int32), N_c, D,
+                                       C.c_int64(q_max), N_b, _p(out, C.c_int32))
+    assert n >= 0
+    return out[:n].copy()
+
+
+def select_pairs_blocks(Sb_h, B, B_r: int, N_b: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Token-level form of the block selection for one head (tiny L): (I [N_r, N_b], cnt [N_r])."""
+    Sb_h = _f64(Sb_h); B = _i32(B)
+    N_c = B.shape[0] - 1
+    L = int(B[-1])
+    N_r = (L + B_r - 1) // B_r
+    assert Sb_h.shape == (N_r, N_c)
+    I = np.empty((N_r, N_b), dtype=np.int32)
+    cnt = np.empty(N_r, dtype=np.int32)
+    rc = lib().dhsa_oracle_select_pairs_blocks(_p(Sb_h, C.c_double), _p(B, C.c_int32), N_c, B_r, N_b,
+                                               _p(I, C.c_int32), _p(cnt, C.c_int32))
+    assert rc == 0
+    return I, cnt
+
+
+def route_blocks(Q, K, B, B_r: int, N_b: int, blocks) -> Tuple[np.ndarray, np.ndarray]:
+    """Index lists of the given row blocks for every query head: (I [H_q, n, N_b] (-1 padded), cnt [H_q, n])."""
+    Q = _f32(Q); K = _f32(K); B = _i32(B)
+    blocks = np.ascontiguousarray(blocks, dtype=np.int64)
+    H_q, L, D = Q.shape
+    H_kv = K.shape[0]
+    n = blocks.shape[0]
+    I = np.empty((H_q, n, N_b), dtype=np.int32)
+    cnt = np.empty((H_q, n), dtype=np.int32)
+    rc = lib().dhsa_oracle_route_blocks(_p(Q, C.c_float), _p(K, C.c_float), H_q, H_kv, C.c_int64(L), D,
+                                        _p(B, C.c_int32), B.shape[0] - 1, B_r, N_b, _p(blocks, C.c_int64), n,
+                                        _p(I, C.c_int32), _p(cnt, C.c_int32))
+    assert rc == 0
+    return I, cnt
+
+
+def prefill_rows_blocks(Q, K, V, B, B_r: int, N_b: int, rows, scale: Optional[float] = None):
+    """The block-form path on the given rows: (O [H_q, n, D] fp64, I of each row's block, cnt)."""
+    Q = _f32(Q); K = _f32(K); V = _f32(V); B = _i32(B)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    H_q, L, D = Q.shape
+    H_kv = K.shape[0]
+    n = rows.shape[0]
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    O = np.empty((H_q, n, D), dtype=np.float64)
+    I = np.empty((H_q, n, N_b), dtype=np.int32)
+    cnt = np.empty((H_q, n), dtype=np.int32)
+    rc = lib().dhsa_oracle_prefill_rows_blocks(_p(Q, C.c_float), _p(K, C.c_float), _p(V, C.c_float), H_q, H_kv,
+                                               C.c_int64(L), D, _p(B, C.c_int32), B.shape[0] - 1, B_r, N_b,
+                                               C.c_double(scale), _p(rows, C.c_int64), n, _p(O, C.c_double),
+                                               _p(I, C.c_int32), _p(cnt, C.c_int32))
+    assert rc == 0
+    return O, I, cnt
+
+
+def plan_blocks_head(Qb_h, Kc_g, B, B_r: int, N_b: int):
+    """Per row block of one head: tokens listed per key chunk (take [N_r, N_c]) and cut_gap [N_r]."""
+    Qb_h = _f64(Qb_h); Kc_g = _f64(Kc_g); B = _i32(B)
+    N_r, D = Qb_h.shape
+    N_c = B.shape[0] - 1
+    take = np.empty((N_r, N_c), dtype=np.int32)
+    gap = np.empty(N_r, dtype=np.float64)
+    rc = lib().dhsa_oracle_plan_blocks_head(_p(Qb_h, C.c_double), _p(Kc_g, C.c_double), _p(B, C.c_int32), N_c, D,
+                                            B_r, N_b, _p(take, C.c_int32), _p(gap, C.c_double))
+    assert rc == 0
+    return take, gap

@@ -22,6 +22,12 @@
  *   - Argsort is stable: equal scores -> lower chunk id first (hence lower key index);
  *   - GQA: routing per query head h against the pooled keys of kv-head h / G;
  *   - floating point: all sums in fp64 over the exactly-upcast inputs.
+ * The functions whose names end in _blocks state Alg. 1 as printed instead: queries
+ * pooled over fixed row blocks of B_r rows (q_i = sqrt(B_r) AvgPool(Q_i), the mean
+ * taken over the rows the block really has), one index list per row block with
+ * q_max = the block's end, every key chunk ranked, and the causal mask applied
+ * per token inside attention (Alg. 2 / Alg. 3); a row that sees none of its
+ * block's keys gets zeros.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (closed
  * forms, brute force on tiny inputs, library special cases).  The paper prints
@@ -401,6 +407,179 @@ API int dhsa_oracle_plan_head(const double *Qc_h /* [N_c][D] */, const double *K
         }
         cut_gap[l] = gap;
         free(S_row); free(pi); free(before);
+    }
+    return err;
+}
+
+
+/* ======================= Alg. 1 as printed: fixed row blocks ======================= */
+
+/* ---- Alg. 1 step "row-block query representations": q_i = sqrt(B_r) * AvgPool(Q_i),
+ * Q_i = Q[i B_r : min((i+1) B_r, L)).  AvgPool is the mean over the rows the block has
+ * (the last block may be short); the factor is sqrt of the nominal B_r as printed. ---- */
+API int dhsa_oracle_pool_blocks(const float *X, int H, int64_t L, int D, int B_r,
+                                double *Xq /* [H][N_r][D] */) {
+    int64_t N_r = (L + B_r - 1) / B_r;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int h = 0; h < H; ++h) {
+        for (int64_t i = 0; i < N_r; ++i) {
+            int64_t q_s = i * B_r, q_e = (i + 1) * B_r < L ? (i + 1) * B_r : L;
+            for (int d = 0; d < D; ++d) {
+                double sum = 0.0;
+                for (int64_t r = q_s; r < q_e; ++r) sum += (double)X[((int64_t)h * L + r) * D + d];
+                Xq[((int64_t)h * N_r + i) * D + d] = sqrt((double)B_r) * (sum / (double)(q_e - q_s));
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- Alg. 1 for one row block i of one head: S_c[i, :] over ALL key chunks,
+ * Argsort (stable, descending), walk with q_max = min((i+1) B_r, L).  Returns |I_i|. ---- */
+API int dhsa_oracle_select_block(const double *q_i /* [D] */, const double *Kc_g /* [N_c][D] */,
+                                 const int32_t *B, int N_c, int D, int64_t q_max, int N_b,
+                                 int32_t *I /* capacity N_b */) {
+    double *S_row = (double *)malloc((size_t)N_c * sizeof(double));
+    int32_t *pi = (int32_t *)malloc((size_t)N_c * sizeof(int32_t));
+    if (!S_row || !pi) { free(S_row); free(pi); return -1; }
+    dhsa_oracle_score_row(q_i, Kc_g, N_c, D, S_row);
+    int n = dhsa_oracle_rank(S_row, N_c, pi) ? -1 : dhsa_oracle_select(pi, B, N_c, q_max, N_b, I);
+    free(S_row); free(pi);
+    return n;
+}
+
+/* ---- Second, independent form of the block selection (tiny L): every key token
+ * j < q_max inherits the score of (row block i, chunk of j); keep the N_b best,
+ * larger score first, equal scores -> lower key index; sort ascending. ---- */
+API int dhsa_oracle_select_pairs_blocks(const double *Sb_h /* [N_r][N_c] */, const int32_t *B, int N_c,
+                                        int B_r, int N_b, int32_t *I /* [N_r][N_b], -1 padded */,
+                                        int32_t *cnt /* [N_r] */) {
+    int64_t L = B[N_c];
+    int64_t N_r = (L + B_r - 1) / B_r;
+    int32_t *chunk_of = (int32_t *)malloc((size_t)L * sizeof(int32_t));
+    pair_t *row = (pair_t *)malloc((size_t)L * sizeof(pair_t));
+    if (!chunk_of || !row) return 1;
+    for (int k = 0; k < N_c; ++k)
+        for (int64_t j = B[k]; j < B[k + 1]; ++j) chunk_of[j] = k;
+    for (int64_t i = 0; i < N_r; ++i) {
+        int64_t q_max = (i + 1) * B_r < L ? (i + 1) * B_r : L;
+        int64_t n = 0;
+        for (int64_t j = 0; j < q_max; ++j) {
+            row[n].s = Sb_h[i * N_c + chunk_of[j]];
+            row[n].j = (int32_t)j;
+            ++n;
+        }
+        qsort(row, (size_t)n, sizeof(pair_t), cmp_pair);
+        if (n > N_b) n = N_b;
+        for (int64_t t = 0; t < n; ++t) I[i * N_b + t] = row[t].j;
+        qsort(I + i * N_b, (size_t)n, sizeof(int32_t), cmp_i32);
+        for (int64_t t = n; t < N_b; ++t) I[i * N_b + t] = -1;
+        cnt[i] = (int32_t)n;
+    }
+    free(chunk_of);
+    free(row);
+    return 0;
+}
+
+/* Index lists of a list of row blocks, every query head (GQA as above). */
+API int dhsa_oracle_route_blocks(const float *Q, const float *K, int H_q, int H_kv, int64_t L, int D,
+                                 const int32_t *B, int N_c, int B_r, int N_b, const int64_t *blocks,
+                                 int n_blocks, int32_t *I_out /* [H_q][n_blocks][N_b], -1 padded */,
+                                 int32_t *cnt_out /* [H_q][n_blocks] */) {
+    int G = H_q / H_kv;
+    int64_t N_r = (L + B_r - 1) / B_r;
+    double *Qb = (double *)malloc((size_t)H_q * N_r * D * sizeof(double));
+    double *Kc = (double *)malloc((size_t)H_kv * N_c * D * sizeof(double));
+    if (!Qb || !Kc) return 1;
+    dhsa_oracle_pool_blocks(Q, H_q, L, D, B_r, Qb);
+    dhsa_oracle_pool(K, H_kv, L, D, B, N_c, Kc);
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H_q; ++h)
+        for (int t = 0; t < n_blocks; ++t) {
+            int64_t i = blocks[t];
+            int64_t q_max = (i + 1) * B_r < L ? (i + 1) * B_r : L;
+            int32_t *I = I_out + ((int64_t)h * n_blocks + t) * N_b;
+            int n = dhsa_oracle_select_block(Qb + ((int64_t)h * N_r + i) * D, Kc + (int64_t)(h / G) * N_c * D, B,
+                                             N_c, D, q_max, N_b, I);
+            if (n < 0) { err = 1; n = 0; }
+            for (int x = n; x < N_b; ++x) I[x] = -1;
+            cnt_out[(int64_t)h * n_blocks + t] = n;
+        }
+    free(Qb); free(Kc);
+    return err;
+}
+
+/* The whole block-form path for a list of rows: the index list of each row's
+ * block (Alg. 1), then Alg. 2 for the row with its causal mask. */
+API int dhsa_oracle_prefill_rows_blocks(const float *Q, const float *K, const float *V, int H_q, int H_kv,
+                                        int64_t L, int D, const int32_t *B, int N_c, int B_r, int N_b,
+                                        double scale, const int64_t *rows, int n_rows,
+                                        double *O_out /* [H_q][n_rows][D] */,
+                                        int32_t *I_out /* [H_q][n_rows][N_b]: the list of the row's block */,
+                                        int32_t *cnt_out) {
+    int G = H_q / H_kv;
+    int64_t *blocks = (int64_t *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int64_t));
+    if (!blocks) return 1;
+    for (int t = 0; t < n_rows; ++t) blocks[t] = rows[t] / B_r;
+    int err = dhsa_oracle_route_blocks(Q, K, H_q, H_kv, L, D, B, N_c, B_r, N_b, blocks, n_rows, I_out, cnt_out);
+    free(blocks);
+    if (err) return err;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H_q; ++h)
+        for (int t = 0; t < n_rows; ++t) {
+            int64_t i = rows[t];
+            int g = h / G;
+            if (dhsa_oracle_attend_row(Q + ((int64_t)h * L + i) * D, K + (int64_t)g * L * D,
+                                       V + (int64_t)g * L * D, I_out + ((int64_t)h * n_rows + t) * N_b,
+                                       cnt_out[(int64_t)h * n_rows + t], i, D, scale,
+                                       O_out + ((int64_t)h * n_rows + t) * D))
+                err = 1;
+        }
+    return err;
+}
+
+/* Per row block of one query head: how many tokens of each key chunk the block's
+ * list holds (they are the chunk's first take[i][k] tokens; 0 = not listed), for
+ * checking a compact plan on ALL blocks at full size; and the smallest score gap
+ * between two adjacently ranked visible chunks whose order changes the list
+ * (rank r is taken and ranks r, r+1 are not both taken whole). */
+API int dhsa_oracle_plan_blocks_head(const double *Qb_h /* [N_r][D] */, const double *Kc_g /* [N_c][D] */,
+                                     const int32_t *B, int N_c, int D, int B_r, int N_b,
+                                     int32_t *take /* [N_r][N_c] */, double *cut_gap /* [N_r] */) {
+    int64_t L = B[N_c];
+    int64_t N_r = (L + B_r - 1) / B_r;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < N_r; ++i) {
+        double *S_row = (double *)malloc((size_t)N_c * sizeof(double));
+        int32_t *pi = (int32_t *)malloc((size_t)N_c * sizeof(int32_t));
+        if (!S_row || !pi) { err = 1; free(S_row); free(pi); continue; }
+        int64_t q_max = (i + 1) * B_r < L ? (i + 1) * B_r : L;
+        dhsa_oracle_score_row(Qb_h + i * D, Kc_g, N_c, D, S_row);
+        dhsa_oracle_rank(S_row, N_c, pi);
+        int32_t *tk = take + i * N_c;
+        for (int k = 0; k < N_c; ++k) tk[k] = 0;
+        int64_t appended = 0;
+        double gap = INFINITY;
+        int prev = -1;
+        int64_t prev_len = 0, prev_take = 0;
+        for (int r = 0; r < N_c; ++r) {
+            int k = pi[r];
+            int64_t s = B[k] < q_max ? B[k] : q_max, e = B[k + 1] < q_max ? B[k + 1] : q_max;
+            if (s >= e) continue;
+            int64_t room = (int64_t)N_b - appended;
+            int64_t t = room <= 0 ? 0 : (room < e - s ? room : e - s);
+            tk[k] = (int32_t)t;
+            if (prev >= 0 && prev_take > 0 && !(prev_take == prev_len && t == e - s)) {
+                double g = fabs(S_row[prev] - S_row[k]);
+                if (g < gap) gap = g;
+            }
+            prev = k; prev_len = e - s; prev_take = t;
+            appended += e - s;
+        }
+        cut_gap[i] = gap;
+        free(S_row); free(pi);
     }
     return err;
 }

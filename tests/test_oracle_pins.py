@@ -391,3 +391,169 @@ def test_plan_head_matches_chunk_walk_and_flags_planted_near_tie():
             assert gap2[l] == 0.0
             hits += 1
     assert hits > 0
+
+
+# ----------------------------------------------------------------------------
+# Alg. 1 as printed (fixed row blocks): hand-worked example, closed forms, brute force
+# ----------------------------------------------------------------------------
+def _evb(x):
+    if isinstance(x, str):
+        return eval(x, {"sqrt2": math.sqrt(2.0), "sqrt3": math.sqrt(3.0), "a": math.exp(-3 * math.sqrt(2.0))})
+    return float(x)
+
+
+@pytest.fixture(scope="module")
+def hand_blocks():
+    with open(os.path.join(HERE, "golden", "hand_example_blocks.json")) as f:
+        return json.load(f)
+
+
+def test_hand_blocks(hand_blocks):
+    hb = hand_blocks
+    B = np.array(hb["B"], dtype=np.int32)
+    B_r = hb["B_r"]
+    Q = np.array(hb["Q"], dtype=np.float32)[None]
+    K = np.array(hb["K"], dtype=np.float32)[None]
+    V = np.array(hb["V"], dtype=np.float32)[None]
+    Qb = oracle.pool_blocks(Q, B_r)
+    np.testing.assert_allclose(Qb[0], [[_evb(v) for v in r] for r in hb["Qb"]], rtol=0, atol=1e-15)
+    Kc = oracle.pool(K, B)
+    Sb = Qb[0] @ Kc[0].T
+    np.testing.assert_allclose(Sb, [[_evb(v) for v in r] for r in hb["Sb"]], rtol=0, atol=1e-14)
+    for i, want in hb["rank_block"].items():
+        assert oracle.rank(Sb[int(i)]).tolist() == want
+    blocks = np.arange(3)
+    for nb, key in ((3, "I_Nb3"), (2, "I_Nb2"), (1, "I_Nb1")):
+        I, cnt = oracle.route_blocks(Q, K, B, B_r, nb, blocks)
+        I2, cnt2 = oracle.select_pairs_blocks(Sb, B, B_r, nb)
+        for i in range(3):
+            assert I[0, i, :cnt[0, i]].tolist() == hb[key][str(i)], (nb, i)
+            q_max = min((i + 1) * B_r, 7)
+            assert oracle.select_block(Qb[0, i], Kc[0], B, q_max, nb).tolist() == hb[key][str(i)]
+        np.testing.assert_array_equal(I[0], I2)
+        np.testing.assert_array_equal(cnt[0], cnt2)
+    for nb, key in ((3, "O_Nb3"), (1, "O_Nb1")):
+        rows = np.array(sorted(int(r) for r in hb[key]))
+        O, _, _ = oracle.prefill_rows_blocks(Q, K, V, B, B_r, nb, rows)
+        for t, r in enumerate(rows):
+            np.testing.assert_allclose(O[0, t], [_evb(v) for v in hb[key][str(r)]], rtol=0, atol=1e-15)
+
+
+def test_pool_blocks_is_scaled_mean_with_a_ragged_last_block():
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((3, 37, 4)).astype(np.float32)
+    for B_r in (1, 5, 8, 37, 64):
+        got = oracle.pool_blocks(X, B_r)
+        starts = np.arange(0, 37, B_r)
+        for i, s in enumerate(starts):
+            e = min(s + B_r, 37)
+            want = math.sqrt(B_r) * X[:, s:e].astype(np.float64).mean(axis=1)
+            np.testing.assert_allclose(got[:, i], want, rtol=1e-14, atol=1e-15)
+    # B_r = 1: the block representation is the row itself
+    np.testing.assert_allclose(oracle.pool_blocks(X, 1), X.astype(np.float64), rtol=0, atol=0)
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.integers(0, 10**6), st.integers(2, 48), st.integers(1, 9), st.integers(1, 12), st.integers(1, 50),
+       st.booleans())
+def test_block_selection_equals_token_level_brute_force(seed, L, B_r, hi, N_b, tied):
+    rng = np.random.default_rng(seed)
+    B = rand_boundaries(rng, L, 1, hi)
+    N_c = len(B) - 1
+    H_q, H_kv, D = 2, 1, 4
+    Q = rng.standard_normal((H_q, L, D)).astype(np.float32)
+    K = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    if tied:   # equal chunk scores: quantise so that ties occur
+        Q = np.round(Q); K = np.round(K)
+    N_r = (L + B_r - 1) // B_r
+    I, cnt = oracle.route_blocks(Q, K, B, B_r, N_b, np.arange(N_r))
+    Qb, Kc = oracle.pool_blocks(Q, B_r), oracle.pool(K, B)
+    for h in range(H_q):
+        Sb = np.stack([Qb[h, i] @ Kc[0].T for i in range(N_r)])
+        # the oracle's own score routine sums in index order: use it so that ties are identical
+        Sb = np.stack([_score_row(Qb[h, i], Kc[0]) for i in range(N_r)])
+        I2, cnt2 = oracle.select_pairs_blocks(Sb, B, B_r, N_b)
+        np.testing.assert_array_equal(I[h], I2)
+        np.testing.assert_array_equal(cnt[h], cnt2)
+        for i in range(N_r):
+            q_max = min((i + 1) * B_r, L)
+            assert cnt[h, i] == min(N_b, q_max)
+            sel = I[h, i, :cnt[h, i]]
+            assert np.all(np.diff(sel) > 0) and sel[-1] < q_max
+        # the per-chunk take counts reproduce the lists (each listed chunk contributes its first tokens)
+        take, _ = oracle.plan_blocks_head(Qb[h], Kc[0], B, B_r, N_b)
+        for i in range(N_r):
+            rebuilt = np.concatenate([np.arange(B[k], B[k] + take[i, k]) for k in range(N_c)]) if N_c else []
+            np.testing.assert_array_equal(rebuilt, I[h, i, :cnt[h, i]])
+
+
+def _score_row(q, Kc):
+    import ctypes as C
+    q = np.ascontiguousarray(q, dtype=np.float64); Kc = np.ascontiguousarray(Kc, dtype=np.float64)
+    out = np.empty(Kc.shape[0], dtype=np.float64)
+    oracle.lib().dhsa_oracle_score_row(q.ctypes.data_as(C.POINTER(C.c_double)), Kc.ctypes.data_as(C.POINTER(C.c_double)),
+                                       Kc.shape[0], Kc.shape[1], out.ctypes.data_as(C.POINTER(C.c_double)))
+    return out
+
+
+def test_blocks_that_coincide_with_chunks_reduce_to_the_row_form():
+    """With every chunk exactly one row block, sqrt(B_r) AvgPool is Eq. 4, so S_c is the same matrix and the
+    list of row block i is the per-row list of the block's LAST row (q_max = block end = i_last + 1)."""
+    rng = np.random.default_rng(11)
+    B_r, N_r, D = 6, 9, 8
+    L = B_r * N_r
+    B = np.arange(0, L + 1, B_r, dtype=np.int32)
+    Q = rng.standard_normal((2, L, D)).astype(np.float32)
+    K = rng.standard_normal((1, L, D)).astype(np.float32)
+    np.testing.assert_allclose(oracle.pool_blocks(Q, B_r), oracle.pool(Q, B), rtol=1e-15, atol=1e-15)
+    for N_b in (1, 5, 17, 60):
+        Ib, cb = oracle.route_blocks(Q, K, B, B_r, N_b, np.arange(N_r))
+        last = np.arange(B_r - 1, L, B_r)
+        Ir, cr = oracle.route_rows(Q, K, B, N_b, last)
+        np.testing.assert_array_equal(cb, cr)
+        np.testing.assert_array_equal(Ib, Ir)
+
+
+def test_block_form_with_a_budget_of_everything_is_dense_causal_attention():
+    rng = np.random.default_rng(13)
+    H_q, H_kv, L, D, B_r = 4, 2, 45, 8, 7
+    B = rand_boundaries(rng, L, 2, 9)
+    Q = rng.standard_normal((H_q, L, D)).astype(np.float32)
+    K = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    V = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    rows = np.arange(L)
+    O, I, cnt = oracle.prefill_rows_blocks(Q, K, V, B, B_r, L + 3, rows)
+    for i in rows:
+        q_max = min((i // B_r + 1) * B_r, L)
+        assert cnt[0, i] == q_max and I[0, i, :q_max].tolist() == list(range(q_max))
+    q, k, v = (torch.from_numpy(x.astype(np.float64)) for x in (Q, K, V))
+    k = k.repeat_interleave(H_q // H_kv, 0); v = v.repeat_interleave(H_q // H_kv, 0)
+    want = torch.nn.functional.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True)[0].numpy()
+    np.testing.assert_allclose(O, want, rtol=1e-12, atol=1e-12)
+
+
+def test_block_form_alg3_equals_alg2_and_rows_without_a_visible_key_are_zero():
+    L, D, B_r, N_b = 40, 8, 8, 3
+    scale = 1.0 / math.sqrt(D)
+    saw_empty = 0
+    for seed in range(6):
+        rng = np.random.default_rng(100 + seed)
+        B = rand_boundaries(rng, L, 1, 6)
+        Q = rng.standard_normal((1, L, D)).astype(np.float32)
+        K = rng.standard_normal((1, L, D)).astype(np.float32)
+        V = rng.standard_normal((1, L, D)).astype(np.float32)
+        rows = np.arange(L)
+        O, I, cnt = oracle.prefill_rows_blocks(Q, K, V, B, B_r, N_b, rows)
+        for blk in range(L // B_r):
+            q_s, q_e = blk * B_r, (blk + 1) * B_r
+            sel = I[0, q_s, :cnt[0, q_s]]
+            for B_c in (1, 2, 64):
+                O3 = oracle.attend_block_tiled(Q[0], K[0], V[0], sel, q_s, q_e, scale, B_c)
+                np.testing.assert_allclose(O3, O[0, q_s:q_e], rtol=1e-12, atol=1e-13)
+            for i in range(q_s, q_e):
+                if sel[0] > i:      # the row precedes every key of its block's list
+                    saw_empty += 1
+                    assert np.all(O[0, i] == 0.0)
+                else:
+                    assert np.any(O[0, i] != 0.0)
+    assert saw_empty > 0
