@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", help="c1..c5 (the metric is quoted on c3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-block-form", action="store_true",
+                    help="skip the extra measurement of Alg. 1 as printed (row blocks of 128 rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -59,32 +61,38 @@ def main() -> int:
     w = dhsa_inputs.make(args.workload)
     Q, K, V = (t.cuda() for t in (w.Q, w.K, w.V))
     O = torch.empty_like(Q)
-    prob = dhsa.problem(Q, K, w.B, w.N_b)
-    plan, ws = dhsa.alloc(prob, w.B)
-    torch.cuda.synchronize()
 
-    def step(ev=None):
-        dhsa.dhsa_route(prob, Q, K, w.B, plan, ws)
-        if ev is not None:
-            ev[0].record()
-        dhsa.dhsa_sparse_prefill(prob, Q, K, V, w.B, plan, O)
-        if ev is not None:
-            ev[1].record()
+    def measure(B_r):
+        """W warm-up steps, then K timed steps of route + sparse attention: (ms/step, attention ms, wall ms)."""
+        prob = dhsa.problem(Q, K, w.B, w.N_b, B_r=B_r)
+        plan, ws = dhsa.alloc(prob, w.B)
+        torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for k in range(args.steps):
-        step(evs[k])
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        def step(ev=None):
+            dhsa.dhsa_route(prob, Q, K, w.B, plan, ws)
+            if ev is not None:
+                ev[0].record()
+            dhsa.dhsa_sparse_prefill(prob, Q, K, V, w.B, plan, O)
+            if ev is not None:
+                ev[1].record()
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for k in range(args.steps):
+            step(evs[k])
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms = e0.elapsed_time(e1) / args.steps
+        return ms, float(np.mean([a.elapsed_time(b) for a, b in evs])), wall
+
+    ms_per_step, attn_ms, wall_ms = measure(0)
     route_ms = ms_per_step - attn_ms
 
     flops = 4.0 * w.D * w.pairs_per_head() * w.H_q          # selected (row, key) pairs only
@@ -109,6 +117,20 @@ def main() -> int:
                      "traffic_detail": MEASURED_TRAFFIC_C3 if args.workload == "c3" else None},
         "paper_context": PAPER_CONTEXT,
     }
+    if not args.no_block_form:
+        # Alg. 1 as printed on the same tensors: row blocks of B_r = 128 rows, one list of N_b keys per block,
+        # causal mask per token.  Listed (row, key) pairs: sum over blocks of rows x min(N_b, block end);
+        # the pairs the causal mask removes inside a block's own range are not subtracted (< 1 % here).
+        B_r = 128
+        ms_b, attn_b, _ = measure(B_r)
+        ends = np.minimum((np.arange((w.L + B_r - 1) // B_r) + 1) * B_r, w.L)
+        rows_b = np.diff(np.r_[0, ends])
+        pairs_b = float((rows_b * np.minimum(min(w.N_b, w.L), ends)).sum())
+        fl_b = 4.0 * w.D * pairs_b * w.H_q
+        out["alg1_block_form"] = {"B_r": B_r, "ms_per_layer": round(ms_b, 4), "sparse_attention_ms": round(attn_b, 4),
+                                  "route_ms": round(ms_b - attn_b, 4), "flop_listed_pairs": fl_b,
+                                  "achieved_tflops": round(fl_b / (attn_b * 1e-3) / 1e12, 3),
+                                  "frac_of_bf16_mfma_peak": round(fl_b / (attn_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5)}
     # what the matrix unit alone sustains on this chip (same instruction as the attention kernel):
     # with operands that never change, and with random operands (the chip then clocks down to stay
     # inside its power limit, as it does on real attention data)

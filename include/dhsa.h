@@ -18,6 +18,16 @@
  * Steps 1-4 are dhsa_route (result: a compact routing plan), step 5 is
  * dhsa_sparse_prefill, dhsa_prefill runs both on one stream.
  *
+ * With B_r > 0 in the problem struct the same entry points run Alg. 1 as it is
+ * printed (App. C) instead of the per-row form above: queries are grouped in
+ * fixed row blocks of B_r rows, q_i = sqrt(B_r) * AvgPool(Q_i) (mean over the
+ * rows the block has), S_c is N_r x N_c with N_r = ceil(L / B_r), every key
+ * chunk is ranked, ONE index list per row block is built with q_max = the
+ * block's end (at most N_b tokens, the last chunk taken truncated to its lowest
+ * indices), and attention applies the causal mask per token (Alg. 2 / Alg. 3:
+ * row u of block i attends the listed keys j <= i B_r + u).  A row that sees
+ * none of its block's keys gets O = 0.
+ *
  * Conventions
  *   - "dev" pointers are device (HBM) addresses, "host" pointers host addresses.
  *   - Q is [H_q, L, D], K and V are [H_kv, L, D], O is [H_q, L, D]; D contiguous;
@@ -80,6 +90,8 @@ typedef struct {
     int64_t k_stride_h, k_stride_l;
     int64_t v_stride_h, v_stride_l;
     int64_t o_stride_h, o_stride_l;
+    int32_t B_r;              /* 0: per-row budgets on the dynamic chunks (steps 1-5 above);
+                                 > 0: Alg. 1 as printed with row blocks of B_r rows        */
 } dhsa_problem;
 
 /*
@@ -89,24 +101,30 @@ typedef struct {
  * their own chunk.
  *   words [0, 16)            header: magic 'DHSA', version, H_q, N_c, N_b (clamped to L),
  *                            stride, L, T1 (row tiles per head), off_B, off_count,
- *                            off_entries, off_tiles (word offsets), T_big, rest 0
- *   off_B      int32[N_c+1]  the boundaries
+ *                            off_entries, off_tiles (word offsets), T_big, off_RB, N_q, B_r
+ *   off_B      int32[N_c+1]  the boundaries of the key chunks
+ *   off_RB     int32[N_q+1]  the boundaries of the query groups: the same array as
+ *                            off_B (N_q = N_c) when B_r = 0; else RB[i] = min(i B_r, L),
+ *                            N_q = ceil(L / B_r).  Below, "chunk l" on the query side
+ *                            means query group l and v = i + 1 - RB[l].
  *   off_count  int32[H_q][N_c]          number of entries of (h, l)
  *   off_entries int32[H_q][N_c][stride][2]   entries, ascending chunk id:
  *        word 0: key chunk id k | (pos << 28), pos = 0 ranked before chunk l,
- *                1 = chunk l itself, 2 ranked after chunk l
- *        word 1: rem = N_b - (tokens of other chunks taken before chunk k)
+ *                1 = chunk l itself, 2 ranked after chunk l, 3 = row-block form
+ *        word 1: rem = N_b - (tokens of other chunks taken before chunk k); for
+ *                pos = 3 the number of tokens of chunk k in the block's list
  *      Row i of chunk l takes from entry (k, pos, rem) the tokens B[k] + t with
  *        t < min(len_k, rem)            if pos = 0
  *        t < min(v, rem)                if pos = 1
  *        t < min(len_k, rem - v)        if pos = 2
+ *        t < rem and B[k] + t <= i      if pos = 3 (the block's list, causal mask per token)
  *      Only chunks some row of l takes a token from are listed.
  *   off_tiles  int32[T1][2]  row tiles of one head: (chunk l, first row), rows
  *                            [row, min(row + 128, B[l+1])); first the T_big tiles of
  *                            more than 64 rows, then the others, each group by row
  */
 #define DHSA_PLAN_MAGIC 0x41534844
-#define DHSA_PLAN_VERSION 1
+#define DHSA_PLAN_VERSION 2
 #define DHSA_ROW_TILE 128
 
 /* Device bytes the plan / the routing workspace need.  0 on invalid arguments. */
@@ -137,16 +155,18 @@ dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void
 
 /* Expand the plan into explicit index sets I_{h,i} (Alg. 1's output) for one
  * head and a HOST list of rows: idx_dev[n_rows][cap] ascending, padded with -1,
- * cnt_dev[n_rows]; cap >= min(N_b, L).  rows are copied to rows_dev_scratch
+ * cnt_dev[n_rows]; cap >= min(N_b, L).  With B_r > 0 a row gets the list of its
+ * row block as Alg. 1 returns it (not yet masked causally).  rows are copied to rows_dev_scratch
  * (device, n_rows int64) by the call. */
 dhsa_status dhsa_plan_expand_rows(const dhsa_problem *prob, const void *plan_dev, size_t plan_bytes,
                                   int32_t head, const int64_t *rows_host, int32_t n_rows,
                                   int64_t *rows_dev_scratch, int32_t *idx_dev, int32_t cap,
                                   int32_t *cnt_dev, void *stream);
 
-/* Copy the pooled vectors (fp64, Qc_dev [H_q][N_c][D], Kc_dev [H_kv][N_c][D])
- * and/or the lower triangle of S_c (fp64, Sc_dev [H_q][N_c][N_c], entries with
- * k > l are not written) out of a workspace dhsa_route has filled.  NULL skips. */
+/* Copy the pooled vectors (fp64, Qc_dev [H_q][N_q][D], Kc_dev [H_kv][N_c][D])
+ * and/or S_c (fp64, Sc_dev [H_q][N_q][N_c]; entries of chunks no row of the
+ * query group can see are not written) out of a workspace dhsa_route has
+ * filled.  N_q = N_c, or ceil(L / B_r) when B_r > 0.  NULL skips. */
 dhsa_status dhsa_debug_routing(const dhsa_problem *prob, const int32_t *B_host, const void *ws_dev,
                                size_t ws_bytes, double *Qc_dev, double *Kc_dev, double *Sc_dev, void *stream);
 

@@ -31,7 +31,8 @@ class dhsa_problem(C.Structure):
                 ("q_stride_h", C.c_int64), ("q_stride_l", C.c_int64),
                 ("k_stride_h", C.c_int64), ("k_stride_l", C.c_int64),
                 ("v_stride_h", C.c_int64), ("v_stride_l", C.c_int64),
-                ("o_stride_h", C.c_int64), ("o_stride_l", C.c_int64)]
+                ("o_stride_h", C.c_int64), ("o_stride_l", C.c_int64),
+                ("B_r", C.c_int32)]
 
 
 class DhsaError(RuntimeError):
@@ -91,15 +92,16 @@ def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
-def problem(Q, K, B, N_b: int, scale: float = 0.0) -> dhsa_problem:
-    """Describe Q [H_q, L, D] and K [H_kv, L, D] (torch tensors, last dim contiguous)."""
+def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0) -> dhsa_problem:
+    """Describe Q [H_q, L, D] and K [H_kv, L, D] (torch tensors, last dim contiguous).
+    B_r > 0 selects Alg. 1 as printed (row blocks of B_r rows, one index list per block)."""
     import torch
     H_q, L, D = Q.shape
     H_kv = K.shape[0]
     dt = {torch.float32: DHSA_F32, torch.bfloat16: DHSA_BF16}.get(Q.dtype, -1)
     return dhsa_problem(L=L, H_q=H_q, H_kv=H_kv, D=D, N_c=len(B) - 1, N_b=N_b, dtype=dt, scale=scale,
                         q_stride_h=Q.stride(0), q_stride_l=Q.stride(1),
-                        k_stride_h=K.stride(0), k_stride_l=K.stride(1))
+                        k_stride_h=K.stride(0), k_stride_l=K.stride(1), B_r=B_r)
 
 
 def dhsa_plan_bytes(prob: dhsa_problem, B) -> int:
@@ -164,14 +166,20 @@ def dhsa_plan_expand_rows(prob, plan, head: int, rows) -> Tuple["torch.Tensor", 
     return idx, cnt
 
 
+def n_query_groups(prob) -> int:
+    """Query groups of the routing: the chunks, or the row blocks when B_r > 0."""
+    return (prob.L + prob.B_r - 1) // prob.B_r if prob.B_r > 0 else prob.N_c
+
+
 def dhsa_debug_routing(prob, B, ws, want_Sc: bool = True):
     """(Q_c, K_c, S_c) fp64 device tensors copied out of a workspace dhsa_route filled."""
     import torch
     B = _b(B)
     dev = ws.device
-    Qc = torch.empty((prob.H_q, prob.N_c, prob.D), dtype=torch.float64, device=dev)
+    N_q = n_query_groups(prob)
+    Qc = torch.empty((prob.H_q, N_q, prob.D), dtype=torch.float64, device=dev)
     Kc = torch.empty((prob.H_kv, prob.N_c, prob.D), dtype=torch.float64, device=dev)
-    Sc = torch.zeros((prob.H_q, prob.N_c, prob.N_c), dtype=torch.float64, device=dev) if want_Sc else None
+    Sc = torch.zeros((prob.H_q, N_q, prob.N_c), dtype=torch.float64, device=dev) if want_Sc else None
     _check(lib().dhsa_debug_routing(C.byref(prob), _bp(B), ws.data_ptr(), ws.numel(), Qc.data_ptr(), Kc.data_ptr(),
                                     Sc.data_ptr() if want_Sc else None, _stream()))
     return Qc, Kc, Sc
@@ -199,8 +207,9 @@ def parse_plan(plan_host: np.ndarray) -> dict:
     assert w[0] == PLAN_MAGIC, "not a DHSA plan"
     H_q, N_c, N_b, stride, L, T1 = (int(x) for x in (w[2], w[3], w[4], w[5], w[6], w[7]))
     oB, oC, oE, oT = (int(x) for x in w[8:12])
-    return dict(H_q=H_q, N_c=N_c, N_b=N_b, stride=stride, L=L, T1=T1, T_big=int(w[12]),
-                B=w[oB:oB + N_c + 1],
-                count=w[oC:oC + H_q * N_c].reshape(H_q, N_c),
-                entries=w[oE:oE + H_q * N_c * stride * 2].reshape(H_q, N_c, stride, 2),
+    oRB, N_q, B_r = int(w[13]), int(w[14]), int(w[15])
+    return dict(H_q=H_q, N_c=N_c, N_b=N_b, stride=stride, L=L, T1=T1, T_big=int(w[12]), N_q=N_q, B_r=B_r,
+                B=w[oB:oB + N_c + 1], RB=w[oRB:oRB + N_q + 1],
+                count=w[oC:oC + H_q * N_q].reshape(H_q, N_q),
+                entries=w[oE:oE + H_q * N_q * stride * 2].reshape(H_q, N_q, stride, 2),
                 tiles=w[oT:oT + 2 * T1].reshape(T1, 2))

@@ -46,7 +46,7 @@ template <> struct RowIO<bf16_t> {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_attn_rowwise(PlanView pv, const T *__restrict__ Q,
                                                       const T *__restrict__ K, const T *__restrict__ V,
-                                                      T *__restrict__ O, int64_t L, int N_c, int G, float scale,
+                                                      T *__restrict__ O, int64_t L, int G, float scale,
                                                       int64_t qs_h, int64_t qs_l, int64_t ks_h, int64_t ks_l,
                                                       int64_t vs_h, int64_t vs_l, int64_t os_h, int64_t os_l) {
     constexpr int EP = RowIO<T>::kPer16;
@@ -62,10 +62,10 @@ __global__ __launch_bounds__(256) void k_attn_rowwise(PlanView pv, const T *__re
     if (!live) return;
     const T *Kg = K + (int64_t)g * ks_h;
     const T *Vg = V + (int64_t)g * vs_h;
-    const int l = chunk_of_row(pv.B, N_c, i);
-    const int v = (int)(i + 1 - pv.B[l]);
-    const int E = pv.count[(int64_t)h * N_c + l];
-    const int32_t *ent = pv.entries + ((int64_t)h * N_c + l) * pv.stride * 2;
+    const int l = chunk_of_row(pv.RB, pv.N_q, i);   // the row's query group
+    const int v = (int)(i + 1 - pv.RB[l]);
+    const int E = pv.count[(int64_t)h * pv.N_q + l];
+    const int32_t *ent = pv.entries + ((int64_t)h * pv.N_q + l) * pv.stride * 2;
     float m_run = -INFINITY, l_lane = 0.f;
     float o[NC];
 #pragma unroll
@@ -74,7 +74,11 @@ __global__ __launch_bounds__(256) void k_attn_rowwise(PlanView pv, const T *__re
         const int w0 = ent[2 * e], rem = ent[2 * e + 1];
         const int k = w0 & kChunkMask, pos = w0 >> kPosShift;
         const int b0 = pv.B[k];
-        const int take = entry_take(pos, rem, pv.B[k + 1] - b0, v);
+        int take = entry_take(pos, rem, pv.B[k + 1] - b0, v);
+        if (pos == 3) {   // row-block form: of the block's list, the keys up to the row itself
+            const int64_t vis = i + 1 - b0;
+            if (vis < take) take = vis > 0 ? (int)vis : 0;
+        }
         for (int t0 = 0; t0 < take; t0 += 64) {
             const int nv = (take - t0 < 64) ? take - t0 : 64;
             float s = -INFINITY;
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256) void k_attn_rowwise(PlanView pv, const T *__re
     float lsum = l_lane;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off);
-    const float inv = 1.f / lsum;
+    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;   // a row that sees no key of its block's list: zeros
 #pragma unroll
     for (int c = 0; c < NC; ++c)
         RowIO<T>::store(O + (int64_t)h * os_h + i * os_l + lane + 64 * c, o[c] * inv);
@@ -118,7 +122,7 @@ hipError_t launch_attn_rowwise(const Prob &p, const PlanView &pv, const void *Q,
     dim3 grid((unsigned)((p.L + 3) / 4), p.H_q), block(256);
 #define DHSA_ROWWISE(T, DD)                                                                                  \
     hipLaunchKernelGGL((k_attn_rowwise<T, DD>), grid, block, 0, s, pv, (const T *)Q, (const T *)K,           \
-                       (const T *)V, (T *)O, p.L, p.N_c, p.G, p.scale, p.qs_h, p.qs_l, p.ks_h, p.ks_l,       \
+                       (const T *)V, (T *)O, p.L, p.G, p.scale, p.qs_h, p.qs_l, p.ks_h, p.ks_l,              \
                        p.vs_h, p.vs_l, p.os_h, p.os_l)
     if (p.dtype == DHSA_F32) {
         if (p.D == 64) DHSA_ROWWISE(float, 64); else DHSA_ROWWISE(float, 128);

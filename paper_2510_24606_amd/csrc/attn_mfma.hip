@@ -121,7 +121,7 @@ template <int D, bool PAR>
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, int T, const uint16_t *__restrict__ Q,
                                                       const uint16_t *__restrict__ K,
                                                       const uint16_t *__restrict__ V, uint16_t *__restrict__ O,
-                                                      int N_c, int H_q, int G, int mode,
+                                                      int H_q, int G, int mode,
                                                       float scale_log2e, int64_t qs_h, int64_t qs_l,
                                                       int64_t ks_h, int64_t ks_l, int64_t vs_h, int64_t vs_l,
                                                       int64_t os_h, int64_t os_l) {
@@ -141,9 +141,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     decode_block(mode, blockIdx.x, H_q, G, T, &h, &tile);
     tile += tile0;   // this launch covers tiles [tile0, tile0 + T) of the plan's table
     const int g = h / G;
-    const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];
-    const int b_l = pv.B[l];
-    const int rows_left = pv.B[l + 1] - row0;
+    const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];   // query group, first row
+    const int b_l = pv.RB[l];
+    const int rows_left = pv.RB[l + 1] - row0;
     const int nrows = rows_left < kRowTile ? rows_left : kRowTile;
     const int v_lo = row0 + 1 - b_l, v_hi = v_lo + nrows - 1;
     // Wave roles (PAR = false / true is chosen per launch: the plan lists the tiles
@@ -187,8 +187,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
     float m_ref = pad_row ? 1e30f : -INFINITY, l_run = 0.f;   // m_ref: reference used in the exponent (see DHSA_EXP)
 
-    const int E = pv.count[(int64_t)h * N_c + l];
-    const int32_t *ent = pv.entries + ((int64_t)h * N_c + l) * pv.stride * 2;
+    const int E = pv.count[(int64_t)h * pv.N_q + l];
+    const int32_t *ent = pv.entries + ((int64_t)h * pv.N_q + l) * pv.stride * 2;
 
     // staging: load instruction c of this wave fills LDS window (4 c + wave) of a
     // tile (1 KiB = 64 pieces); this lane's piece there is physical piece
@@ -233,6 +233,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             const int b0 = pv.B[k];
             // most tokens any row of the tile takes from this chunk
             n_e = entry_take(pos, rem, pv.B[k + 1] - b0, pos == 1 ? v_hi : v_lo);
+            if (pos == 3) {   // row-block form: keys past the tile's last row are masked for every row
+                const int vis = row0 + nrows - b0;
+                n_e = vis < n_e ? (vis > 0 ? vis : 0) : n_e;
+            }
             sm.seg_b0[tid] = b0;
             sm.seg_pos[tid] = pos;
             sm.seg_rem[tid] = rem;
@@ -263,10 +267,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         const int seg_ = 16 * c_ + f_;                                                          \
         const int t_ = x_ - sm.seg_start[seg_];                                                 \
         const int pos_ = sm.seg_pos[seg_];                                                      \
-        int lo_ = (pos_ == 1) ? t_ : 0;                                                         \
+        const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
+        /* key j is at or below row i  <=>  j - b_l < v: the group's own chunk (pos 1,   */     \
+        /* j - b_l = t) and every listed key of the row-block form (pos 3) */                   \
+        int lo_ = (pos_ & 1) ? ((int)j_ > b_l ? (int)j_ - b_l : 0) : 0;                         \
         int hi_ = (pos_ == 2) ? sm.seg_rem[seg_] - t_ : kIntMax;                                \
         if (pad_) { lo_ = kIntMax; hi_ = kIntMax; }                                             \
-        const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
         sm.key_koff[buf_][off_slot_wr] = j_ * k_row_bytes;                                      \
         sm.key_voff[buf_][off_slot_wr] = j_ * v_row_bytes;                                      \
         sm.key_lo[buf_][lane] = lo_;                                                            \
@@ -607,7 +613,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         const int r = rb * 32 + lr;
         if (r < nrows) {
-            const float inv = 1.f / l_tot;
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;   // no visible key (row-block form): zeros
             uint16_t *op = O + (int64_t)h * os_h + (int64_t)(row0 + r) * os_l;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
@@ -634,7 +640,7 @@ hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, co
         const int mode = attn_order(want, p.H_kv, p.G, T);                                                  \
         hipLaunchKernelGGL((k_attn_mfma<DD, PAR>), dim3(p.H_q * (T)), dim3(256), 0, s, pv, tile0, T,        \
                            (const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O,    \
-                           p.N_c, p.H_q, p.G, mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l,      \
+                           p.H_q, p.G, mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l,      \
                            p.os_h, p.os_l);                                                                 \
     }
     // tiles of more than 64 rows first (they take longest), then the key-parity tiles

@@ -23,12 +23,17 @@ dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
     if (in->D != 64 && in->D != 128) return DHSA_ERR_SHAPE;
     if (in->N_c < 1 || in->N_c > kMaxChunks || in->N_c > in->L) return DHSA_ERR_SHAPE;
     if (in->N_b < 1) return DHSA_ERR_BUDGET;
+    if (in->B_r < 0) return DHSA_ERR_SHAPE;
+    // row-block form: N_r = ceil(L / B_r) query groups, one workgroup each in the ranking kernel
+    if (in->B_r > 0 && (in->L + in->B_r - 1) / in->B_r > (int64_t)1 << 20) return DHSA_ERR_SHAPE;
     if (!(in->scale >= 0.f) || !isfinite(in->scale)) return DHSA_ERR_SHAPE;
     if (B[0] != 0 || (int64_t)B[in->N_c] != in->L) return DHSA_ERR_BOUNDARIES;
     for (int k = 0; k < in->N_c; ++k)
         if (B[k + 1] <= B[k]) return DHSA_ERR_BOUNDARIES;
     p->L = in->L; p->H_q = in->H_q; p->H_kv = in->H_kv; p->G = in->H_q / in->H_kv; p->D = in->D;
     p->N_c = in->N_c;
+    p->B_r = in->B_r;
+    p->N_q = in->B_r > 0 ? (int)((in->L + in->B_r - 1) / in->B_r) : in->N_c;
     p->N_b = (int)std::min<int64_t>(in->N_b, in->L);
     p->dtype = in->dtype;
     p->scale = in->scale > 0.f ? in->scale : 1.0f / sqrtf((float)in->D);
@@ -56,24 +61,35 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     // most chunks any query chunk can list: the chunks taken before the budget
     // is met number at most 1 + (how many of the shortest chunks sum to < N_b),
     // plus the query chunk itself
+    // (in the row-block form the chunk cut by the block's end may count with any
+    // shorter length: it is the "+ 1" that is not among the whole chunks)
     std::vector<int32_t> lens(p.N_c);
-    int T1 = 0, T_big = 0;
-    for (int k = 0; k < p.N_c; ++k) {
-        lens[k] = B[k + 1] - B[k];
-        T1 += (lens[k] + kRowTile - 1) / kRowTile;
-        T_big += lens[k] / kRowTile + (lens[k] % kRowTile > kRowTile / 2);
+    for (int k = 0; k < p.N_c; ++k) lens[k] = B[k + 1] - B[k];
+    int64_t T1 = 0, T_big = 0;
+    if (p.B_r > 0) {
+        const int64_t full = p.L / p.B_r, tail = p.L % p.B_r;     // row blocks of B_r rows, one shorter block
+        T1 = full * ((p.B_r + kRowTile - 1) / kRowTile) + (tail + kRowTile - 1) / kRowTile;
+        T_big = full * (p.B_r / kRowTile + (p.B_r % kRowTile > kRowTile / 2)) +
+                tail / kRowTile + (tail % kRowTile > kRowTile / 2);
+    } else {
+        for (int k = 0; k < p.N_c; ++k) {
+            T1 += (lens[k] + kRowTile - 1) / kRowTile;
+            T_big += lens[k] / kRowTile + (lens[k] % kRowTile > kRowTile / 2);
+        }
     }
     std::sort(lens.begin(), lens.end());
     int64_t acc = 0;
     int n = 0;
     while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
     pl.stride = std::min(p.N_c, n + 2);
-    pl.T1 = T1;
-    pl.T_big = T_big;
+    pl.T1 = (int)T1;
+    pl.T_big = (int)T_big;
+    pl.N_q = p.N_q;
     pl.off_B = 16;
-    pl.off_count = align_up(pl.off_B + p.N_c + 1, 4);
-    pl.off_entries = align_up(pl.off_count + (int64_t)p.H_q * p.N_c, 4);
-    pl.off_tiles = align_up(pl.off_entries + (int64_t)p.H_q * p.N_c * pl.stride * 2, 4);
+    pl.off_RB = p.B_r > 0 ? align_up(pl.off_B + p.N_c + 1, 4) : pl.off_B;
+    pl.off_count = align_up(pl.off_RB + p.N_q + 1, 4);
+    pl.off_entries = align_up(pl.off_count + (int64_t)p.H_q * p.N_q, 4);
+    pl.off_tiles = align_up(pl.off_entries + (int64_t)p.H_q * p.N_q * pl.stride * 2, 4);
     pl.words = align_up(pl.off_tiles + (int64_t)T1 * 2, 64);
     return pl;
 }
@@ -81,9 +97,9 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
 WsLayout ws_layout(const Prob &p) {
     WsLayout w;
     w.off_Qc = 0;
-    w.off_Kc = align_up(w.off_Qc + (int64_t)p.H_q * p.N_c * p.D, 32);
+    w.off_Kc = align_up(w.off_Qc + (int64_t)p.H_q * p.N_q * p.D, 32);
     w.off_Sc = align_up(w.off_Kc + (int64_t)p.H_kv * p.N_c * p.D, 32);
-    w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_c * p.N_c, 32);
+    w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_q * p.N_c, 32);
     return w;
 }
 
@@ -91,12 +107,14 @@ PlanView plan_view(const PlanLayout &pl, const void *plan) {
     const int32_t *w = static_cast<const int32_t *>(plan);
     PlanView v;
     v.B = w + pl.off_B;
+    v.RB = w + pl.off_RB;
     v.count = w + pl.off_count;
     v.entries = w + pl.off_entries;
     v.tiles = w + pl.off_tiles;
     v.stride = pl.stride;
     v.T1 = pl.T1;
     v.T_big = pl.T_big;
+    v.N_q = pl.N_q;
     return v;
 }
 
@@ -110,9 +128,10 @@ dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, 
                                   hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return DHSA_ERR_HIP;
     if ((e = launch_setup(p, pl, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
-    if ((e = launch_pool(p, Q, K, pw + pl.off_B, wd + wl.off_Qc, wd + wl.off_Kc, s)) != hipSuccess)
+    if ((e = launch_pool(p, Q, K, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Qc, wd + wl.off_Kc, s)) != hipSuccess)
         return DHSA_ERR_HIP;
-    if ((e = launch_scores(p, wd + wl.off_Qc, wd + wl.off_Kc, wd + wl.off_Sc, s)) != hipSuccess)
+    if ((e = launch_scores(p, wd + wl.off_Qc, wd + wl.off_Kc, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Sc, s)) !=
+        hipSuccess)
         return DHSA_ERR_HIP;
     if ((e = launch_select(p, pl, wd + wl.off_Sc, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
     return DHSA_OK;
@@ -201,7 +220,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
     int32_t n_rows, int64_t *rows_dev_scratch, int32_t *idx_dev, int32_t cap, int32_t *cnt_dev, void *stream) {
     if (!prob || !plan_dev || !rows_host || !rows_dev_scratch || !idx_dev || !cnt_dev) return DHSA_ERR_NULL;
     // the boundaries live in the plan; only the scalar fields of the problem are checked here
-    if (prob->L < 1 || prob->N_c < 1 || prob->N_c > kMaxChunks || prob->H_q < 1 || prob->N_b < 1)
+    if (prob->L < 1 || prob->N_c < 1 || prob->N_c > kMaxChunks || prob->H_q < 1 || prob->N_b < 1 || prob->B_r < 0)
         return DHSA_ERR_SHAPE;
     if (head < 0 || head >= prob->H_q || n_rows < 0) return DHSA_ERR_SHAPE;
     const int nb = (int)std::min<int64_t>(prob->N_b, prob->L);
@@ -215,16 +234,17 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
     if (hipMemcpyAsync(hdr, plan_dev, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return DHSA_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return DHSA_ERR_HIP;
     if (hdr[0] != DHSA_PLAN_MAGIC || hdr[1] != DHSA_PLAN_VERSION || hdr[2] != prob->H_q || hdr[3] != prob->N_c ||
-        hdr[4] != nb || (int64_t)hdr[6] != prob->L)
+        hdr[4] != nb || (int64_t)hdr[6] != prob->L || hdr[15] != prob->B_r ||
+        hdr[14] != (prob->B_r > 0 ? (int32_t)((prob->L + prob->B_r - 1) / prob->B_r) : prob->N_c))
         return DHSA_ERR_PLAN;
     PlanLayout pl;
-    pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12];
-    pl.off_B = hdr[8]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
+    pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12]; pl.N_q = hdr[14];
+    pl.off_B = hdr[8]; pl.off_RB = hdr[13]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
     pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
     Prob p;
     memset(&p, 0, sizeof(p));
-    p.L = prob->L; p.H_q = prob->H_q; p.N_c = prob->N_c; p.N_b = nb;
+    p.L = prob->L; p.H_q = prob->H_q; p.N_c = prob->N_c; p.N_b = nb; p.B_r = prob->B_r; p.N_q = pl.N_q;
     if (n_rows == 0) return DHSA_OK;
     if (hipMemcpyAsync(rows_dev_scratch, rows_host, sizeof(int64_t) * (size_t)n_rows, hipMemcpyHostToDevice, s) !=
         hipSuccess)
@@ -248,13 +268,13 @@ __attribute__((visibility("default"))) dhsa_status dhsa_debug_routing(const dhsa
     const double *wd = static_cast<const double *>(ws_dev);
     hipError_t e = hipSuccess;
     if (Qc_dev)
-        e = hipMemcpyAsync(Qc_dev, wd + wl.off_Qc, sizeof(double) * (size_t)p.H_q * p.N_c * p.D,
+        e = hipMemcpyAsync(Qc_dev, wd + wl.off_Qc, sizeof(double) * (size_t)p.H_q * p.N_q * p.D,
                            hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && Kc_dev)
         e = hipMemcpyAsync(Kc_dev, wd + wl.off_Kc, sizeof(double) * (size_t)p.H_kv * p.N_c * p.D,
                            hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && Sc_dev)
-        e = hipMemcpyAsync(Sc_dev, wd + wl.off_Sc, sizeof(double) * (size_t)p.H_q * p.N_c * p.N_c,
+        e = hipMemcpyAsync(Sc_dev, wd + wl.off_Sc, sizeof(double) * (size_t)p.H_q * p.N_q * p.N_c,
                            hipMemcpyDeviceToDevice, s);
     return hip_status(e);
 }
@@ -275,6 +295,6 @@ __attribute__((visibility("default"))) const char *dhsa_status_string(dhsa_statu
     return "unknown status";
 }
 
-__attribute__((visibility("default"))) int dhsa_version(void) { return 100; }
+__attribute__((visibility("default"))) int dhsa_version(void) { return 110; }
 
 }  // extern "C"

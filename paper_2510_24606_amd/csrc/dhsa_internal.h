@@ -17,6 +17,7 @@ constexpr int kChunkMask = (1 << kPosShift) - 1;
 struct Prob {
     int64_t L;
     int H_q, H_kv, G, D, N_c, N_b;  // N_b already clamped to L
+    int B_r, N_q;                   // row-block size (0 = query groups are the chunks), query groups
     int dtype;
     float scale;
     int64_t qs_h, qs_l, ks_h, ks_l, vs_h, vs_l, os_h, os_l;
@@ -27,16 +28,18 @@ struct PlanLayout {
     int stride;       // entries per (h, l)
     int T1;           // row tiles per head
     int T_big;        // ... of which have more than 64 rows (listed first)
-    int64_t off_B, off_count, off_entries, off_tiles, words;
+    int N_q;          // query groups (chunks, or row blocks)
+    int64_t off_B, off_RB, off_count, off_entries, off_tiles, words;
 };
 
 // Device-side view of a plan.
 struct PlanView {
-    const int32_t *B;        // [N_c + 1]
-    const int32_t *count;    // [H_q][N_c]
-    const int32_t *entries;  // [H_q][N_c][stride][2]
+    const int32_t *B;        // [N_c + 1] key chunk boundaries
+    const int32_t *RB;       // [N_q + 1] query group boundaries (== B when the groups are the chunks)
+    const int32_t *count;    // [H_q][N_q]
+    const int32_t *entries;  // [H_q][N_q][stride][2]
     const int32_t *tiles;    // [T1][2]: first the T_big tiles of more than 64 rows, then the rest
-    int stride, T1, T_big;
+    int stride, T1, T_big, N_q;
 };
 
 // Workspace layout in doubles.
@@ -46,9 +49,10 @@ struct WsLayout {
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
-hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, double *Qc,
-                       double *Kc, hipStream_t s);
-hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, double *Sc, hipStream_t s);
+hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, const int32_t *RB_dev,
+                       double *Qc, double *Kc, hipStream_t s);
+hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, const int32_t *B_dev,
+                         const int32_t *RB_dev, double *Sc, hipStream_t s);
 hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s);
 hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
                          int32_t *idx, int cap, int32_t *cnt, hipStream_t s);
@@ -67,7 +71,9 @@ __device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N
     return lo;
 }
 
-// Tokens row (visible own-chunk count v) takes from a plan entry.
+// Tokens row (visible own-chunk count v) takes from a plan entry.  For pos = 3
+// (row-block form) rem is the number of listed tokens, never above len_k; the
+// causal mask is applied per token by the caller.
 __device__ __forceinline__ int entry_take(int pos, int rem, int len_k, int v) {
     int lim = (pos == 1) ? v : len_k;
     int room = (pos == 2) ? rem - v : rem;

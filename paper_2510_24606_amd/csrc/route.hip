@@ -12,17 +12,28 @@ namespace dhsa {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
-// Plan header + row-tile table.  One block; B is already in the plan.  Tiles
-// are the <= 128-row pieces of the chunks; the table lists first those of more
+// Plan header, query-group boundaries and row-tile table.  One block; B is
+// already in the plan.  The query groups are the chunks themselves, or (Alg. 1
+// as printed) row blocks of B_r rows, RB[i] = min(i B_r, L).  Tiles are the
+// <= 128-row pieces of the query groups; the table lists first those of more
 // than 64 rows, then the others, each group ordered by row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int N_c,
-                                               int N_b, int64_t L) {
+                                               int N_b, int64_t L, int B_r) {
     __shared__ int s_big[256], s_small[256];
     __shared__ int s_carry_big, s_carry_small;
     const int tid = threadIdx.x;
-    const int32_t *B = plan + pl.off_B;
+    const int N_q = pl.N_q;
     int32_t *tiles = plan + pl.off_tiles;
+    if (B_r > 0) {
+        int32_t *RBw = plan + pl.off_RB;
+        for (int i = tid; i <= N_q; i += 256) {
+            const int64_t b = (int64_t)i * B_r;
+            RBw[i] = (int32_t)(b < L ? b : L);
+        }
+        __syncthreads();
+    }
+    const int32_t *B = plan + pl.off_RB;   // the boundaries the rows are grouped by
     if (tid < 16) {
         int32_t w = 0;
         switch (tid) {
@@ -39,16 +50,19 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
             case 10: w = (int32_t)pl.off_entries; break;
             case 11: w = (int32_t)pl.off_tiles; break;
             case 12: w = pl.T_big; break;
+            case 13: w = (int32_t)pl.off_RB; break;
+            case 14: w = N_q; break;
+            case 15: w = B_r; break;
             default: break;
         }
         plan[tid] = w;
     }
     if (tid == 0) { s_carry_big = 0; s_carry_small = pl.T_big; }
     __syncthreads();
-    for (int base = 0; base < N_c; base += 256) {
+    for (int base = 0; base < N_q; base += 256) {
         const int l = base + tid;
         int b0 = 0, len = 0, nfull = 0, rem = 0;
-        if (l < N_c) {
+        if (l < N_q) {
             b0 = B[l];
             len = B[l + 1] - b0;
             nfull = len / kRowTile;
@@ -84,7 +98,7 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
 }
 
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s) {
-    hipLaunchKernelGGL(k_setup, dim3(1), dim3(256), 0, s, plan, pl, p.H_q, p.N_c, p.N_b, p.L);
+    hipLaunchKernelGGL(k_setup, dim3(1), dim3(256), 0, s, plan, pl, p.H_q, p.N_c, p.N_b, p.L, p.B_r);
     return hipGetLastError();
 }
 
@@ -92,6 +106,9 @@ hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipS
 // Chunk pooling, Eq. 4: X_c[h, k, :] = (sqrt(len)/len) * sum_{i in chunk k} X[h, i, :].
 // One block per (chunk, head); a row of D elements is read by D*sizeof(T)/16
 // threads with 16-byte loads, row groups are summed through LDS.  HBM-bound.
+// Keys are pooled over the chunks B; queries over the query groups RB (the
+// chunks again, or with B_r > 0 the row blocks of Alg. 1, whose representation
+// is sqrt(B_r) * mean of the block's rows).
 // ---------------------------------------------------------------------------
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -118,9 +135,10 @@ template <> struct Elem<bf16_t> {
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *__restrict__ K,
-                                              const int32_t *__restrict__ B, double *__restrict__ Qc,
-                                              double *__restrict__ Kc, int H_q, int N_c, int64_t qs_h,
-                                              int64_t qs_l, int64_t ks_h, int64_t ks_l) {
+                                              const int32_t *__restrict__ B, const int32_t *__restrict__ RB,
+                                              double *__restrict__ Qc, double *__restrict__ Kc, int H_q, int N_c,
+                                              int N_q, int B_r, int64_t qs_h, int64_t qs_l, int64_t ks_h,
+                                              int64_t ks_l) {
     constexpr int EPT = Elem<T>::kPer16;   // elements per thread per row
     constexpr int TPR = D / EPT;           // threads per row
     constexpr int RG = 256 / TPR;          // rows in flight
@@ -130,13 +148,16 @@ __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *
     const T *X;
     double *Xc;
     int64_t s_l;
-    if (h < H_q) {
-        X = Q + (int64_t)h * qs_h; s_l = qs_l; Xc = Qc + ((int64_t)h * N_c + k) * D;
+    const bool is_q = h < H_q;
+    if (k >= (is_q ? N_q : N_c)) return;   // block-uniform: the grid spans max(N_q, N_c)
+    if (is_q) {
+        X = Q + (int64_t)h * qs_h; s_l = qs_l; Xc = Qc + ((int64_t)h * N_q + k) * D;
     } else {
         h -= H_q;
         X = K + (int64_t)h * ks_h; s_l = ks_l; Xc = Kc + ((int64_t)h * N_c + k) * D;
     }
-    const int b0 = B[k], b1 = B[k + 1];
+    const int32_t *Bx = is_q ? RB : B;
+    const int b0 = Bx[k], b1 = Bx[k + 1];
     const int tid = threadIdx.x;
     const int rg = tid / TPR, col = (tid % TPR) * EPT;
     double acc[EPT];
@@ -153,17 +174,17 @@ __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *
         double sum = 0.0;
 #pragma unroll 4
         for (int r = 0; r < RG; ++r) sum += s_sum[r][tid];
-        double len = (double)(b1 - b0);
-        Xc[tid] = (sqrt(len) / len) * sum;
+        const double len = (double)(b1 - b0);
+        Xc[tid] = (is_q && B_r > 0) ? sqrt((double)B_r) * (sum / len) : (sqrt(len) / len) * sum;
     }
 }
 
-hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, double *Qc,
-                       double *Kc, hipStream_t s) {
-    dim3 grid(p.N_c, p.H_q + p.H_kv), block(256);
+hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, const int32_t *RB_dev,
+                       double *Qc, double *Kc, hipStream_t s) {
+    dim3 grid(p.N_q > p.N_c ? p.N_q : p.N_c, p.H_q + p.H_kv), block(256);
 #define DHSA_POOL(T, DD)                                                                                  \
-    hipLaunchKernelGGL((k_pool<T, DD>), grid, block, 0, s, (const T *)Q, (const T *)K, B_dev, Qc, Kc,     \
-                       p.H_q, p.N_c, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
+    hipLaunchKernelGGL((k_pool<T, DD>), grid, block, 0, s, (const T *)Q, (const T *)K, B_dev, RB_dev, Qc, \
+                       Kc, p.H_q, p.N_c, p.N_q, p.B_r, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
     if (p.dtype == DHSA_F32) {
         if (p.D == 64) DHSA_POOL(float, 64); else DHSA_POOL(float, 128);
     } else {
@@ -174,22 +195,27 @@ hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_
 }
 
 // ---------------------------------------------------------------------------
-// Chunk similarity S_c[h, l, k] = <Q_c[h, l], K_c[h / G, k]> for k <= l, fp64
-// MFMA (16x16x4).  A 64 x 64 output tile per block; four waves in a 2 x 2
-// arrangement, each 32 x 32 = 2 x 2 MFMA blocks.  Tiles entirely above the
-// diagonal are skipped (those chunk pairs are never visible).
+// Chunk similarity S_c[h, l, k] = <Q_c[h, l], K_c[h / G, k]> for the key chunks
+// k that some row of query group l can see (B[k] < RB[l+1]; with the chunks as
+// query groups that is k <= l), fp64 MFMA (16x16x4).  A 64 x 64 output tile per
+// block; four waves in a 2 x 2 arrangement, each 32 x 32 = 2 x 2 MFMA blocks.
+// Tiles none of whose pairs is visible are skipped.
 // ---------------------------------------------------------------------------
 constexpr int kScTile = 64;
 constexpr int kScKc = 32;   // reduction slab staged in LDS
 constexpr int kScPad = 1;
 
 __global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, const double *__restrict__ Kc,
-                                                double *__restrict__ Sc, int N_c, int D, int G) {
+                                                const int32_t *__restrict__ B, const int32_t *__restrict__ RB,
+                                                double *__restrict__ Sc, int N_c, int N_q, int D, int G) {
     const int k0 = blockIdx.x * kScTile, l0 = blockIdx.y * kScTile, h = blockIdx.z;
-    if (k0 > l0 + kScTile - 1) return;
+    {
+        const int l_last = (l0 + kScTile < N_q ? l0 + kScTile : N_q) - 1;   // last query group of the tile
+        if (B[k0] >= RB[l_last + 1]) return;                                // its first chunk starts past every row
+    }
     __shared__ double sA[kScTile][kScKc + kScPad];
     __shared__ double sB[kScTile][kScKc + kScPad];
-    const double *A = Qc + (int64_t)h * N_c * D;
+    const double *A = Qc + (int64_t)h * N_q * D;
     const double *Bm = Kc + (int64_t)(h / G) * N_c * D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wl = (wave >> 1) * 32, wk = (wave & 1) * 32;
@@ -203,7 +229,7 @@ __global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, c
         // stage 64 x 32 slabs of both operands (rows past N_c read as zero)
         for (int x = tid; x < kScTile * kScKc; x += 256) {
             int r = x / kScKc, c = x % kScKc;
-            sA[r][c] = (l0 + r < N_c) ? A[(int64_t)(l0 + r) * D + d0 + c] : 0.0;
+            sA[r][c] = (l0 + r < N_q) ? A[(int64_t)(l0 + r) * D + d0 + c] : 0.0;
             sB[r][c] = (k0 + r < N_c) ? Bm[(int64_t)(k0 + r) * D + d0 + c] : 0.0;
         }
         __syncthreads();
@@ -232,13 +258,15 @@ __global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, c
             for (int v = 0; v < 4; ++v) {
                 int l = l0 + wl + 16 * m + 4 * v + (lane >> 4);
                 int k = k0 + wk + 16 * n + (lane & 15);
-                if (l < N_c && k < N_c) Sc[((int64_t)h * N_c + l) * N_c + k] = acc[m][n][v];
+                if (l < N_q && k < N_c) Sc[((int64_t)h * N_q + l) * N_c + k] = acc[m][n][v];
             }
 }
 
-hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, double *Sc, hipStream_t s) {
-    int nt = (p.N_c + kScTile - 1) / kScTile;
-    hipLaunchKernelGGL(k_scores, dim3(nt, nt, p.H_q), dim3(256), 0, s, Qc, Kc, Sc, p.N_c, p.D, p.G);
+hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, const int32_t *B_dev,
+                         const int32_t *RB_dev, double *Sc, hipStream_t s) {
+    const int ntk = (p.N_c + kScTile - 1) / kScTile, ntl = (p.N_q + kScTile - 1) / kScTile;
+    hipLaunchKernelGGL(k_scores, dim3(ntk, ntl, p.H_q), dim3(256), 0, s, Qc, Kc, B_dev, RB_dev, Sc, p.N_c, p.N_q,
+                       p.D, p.G);
     return hipGetLastError();
 }
 
@@ -255,25 +283,32 @@ hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, doub
 //      -> rem = N_b - (tokens of other chunks before this rank);
 //   5. a chunk is kept if some row takes a token of it; kept chunks are
 //      compacted in ascending chunk id (prefix sum of flags) into the plan.
+// Row-block form (B_r > 0, Alg. 1 as printed): query group l is a row block,
+// the candidates are the chunks that start before the block's end q_max, their
+// lengths are clipped to q_max, there is no "own chunk", and an entry records
+// how many tokens of the chunk the block's list holds (pos = 3).
 // ---------------------------------------------------------------------------
 constexpr int kMaxCand = 512;     // candidates kept by the radix select
 constexpr int kSelectMin = 512;   // rows with more chunks than this use it (if the LDS allocation has room)
 
 __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
-                                                PlanLayout pl, int N_c, int N_b, int smem_bytes) {
+                                                PlanLayout pl, int N_c, int N_b, int B_r, int smem_bytes) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_wave[4];
     __shared__ int s_p;
     __shared__ int s_hist[256];
     __shared__ int s_digit, s_above, s_equal;
     const int l = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
-    const int n = l + 1;
+    const int32_t *B = plan + pl.off_B;
+    const bool blocks = B_r > 0;
+    const int q_max = blocks ? (plan + pl.off_RB)[l + 1] : 0x7fffffff;   // clip of the chunk lengths
+    const int own = blocks ? -1 : l;                                      // the query group's own chunk
+    const int n = blocks ? chunk_of_row(B, N_c, (int64_t)q_max - 1) + 1 : l + 1;   // visible chunks 0..n-1
     int P = 64;
     while (P < n) P <<= 1;
     unsigned long long *key = reinterpret_cast<unsigned long long *>(smem);  // [P]
     int *id = reinterpret_cast<int *>(smem + (size_t)P * 8);                 // [P]
-    const int32_t *B = plan + pl.off_B;
-    const double *row = Sc + ((int64_t)h * N_c + l) * N_c;
+    const double *row = Sc + ((int64_t)h * pl.N_q + l) * N_c;
 
     for (int x = tid; x < P; x += 256) {
         unsigned long long u = 0ull;
@@ -370,7 +405,7 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     if (tid == 0) s_p = 0x7fffffff;
     __syncthreads();
     for (int x = tid; x < ns; x += 256)
-        if (sid[x] == l) s_p = x;
+        if (sid[x] == own) s_p = x;
     __syncthreads();
     const int p = s_p;
     // the row's key array is dead now: reuse it as rem_by_id / pos_by_id
@@ -388,7 +423,8 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
             int len = 0;
             if (r < ns) {
                 int k = sid[r];
-                len = (k == l) ? 0 : B[k + 1] - B[k];
+                const int e = B[k + 1] < q_max ? B[k + 1] : q_max;
+                len = (k == own) ? 0 : e - B[k];
             }
             lens[e] = len;
             local += len;
@@ -400,9 +436,10 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
             int r = tid * per + e;
             if (r < ns) {
                 int k = sid[r];
-                int pos = (r < p) ? 0 : (r == p ? 1 : 2);
+                int pos = blocks ? 3 : ((r < p) ? 0 : (r == p ? 1 : 2));
                 int rem = N_b - run;                      // may be <= 0: not needed
                 bool need = (pos == 2) ? (rem > 1) : (rem > 0);
+                if (blocks && rem > lens[e]) rem = lens[e];   // tokens of the chunk in the block's list
                 rem_by_id[k] = need ? rem : 0;
                 pos_by_id[k] = pos;
             }
@@ -411,7 +448,7 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     }
     __syncthreads();
     // compact in ascending chunk id
-    int32_t *entries = plan + pl.off_entries + ((int64_t)h * N_c + l) * pl.stride * 2;
+    int32_t *entries = plan + pl.off_entries + ((int64_t)h * pl.N_q + l) * pl.stride * 2;
     {
         const int per_id = P / 256 > 0 ? P / 256 : 1;
         int local = 0;
@@ -431,7 +468,7 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
                 ++slot;
             }
         }
-        if (tid == 0) plan[pl.off_count + (int64_t)h * N_c + l] = total < pl.stride ? total : pl.stride;
+        if (tid == 0) plan[pl.off_count + (int64_t)h * pl.N_q + l] = total < pl.stride ? total : pl.stride;
     }
 }
 
@@ -444,7 +481,8 @@ hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k_select, dim3(p.N_c, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, (int)shmem);
+    hipLaunchKernelGGL(k_select, dim3(p.N_q, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
+                       (int)shmem);
     return hipGetLastError();
 }
 
@@ -456,10 +494,10 @@ __global__ __launch_bounds__(64) void k_expand(PlanView pv, int N_c, int head, c
                                                int32_t *__restrict__ idx, int cap, int32_t *__restrict__ cnt) {
     const int t = blockIdx.x, lane = threadIdx.x;
     const int64_t i = rows[t];
-    const int l = chunk_of_row(pv.B, N_c, i);
-    const int v = (int)(i + 1 - pv.B[l]);
-    const int E = pv.count[(int64_t)head * N_c + l];
-    const int32_t *ent = pv.entries + ((int64_t)head * N_c + l) * pv.stride * 2;
+    const int l = chunk_of_row(pv.RB, pv.N_q, i);
+    const int v = (int)(i + 1 - pv.RB[l]);
+    const int E = pv.count[(int64_t)head * pv.N_q + l];
+    const int32_t *ent = pv.entries + ((int64_t)head * pv.N_q + l) * pv.stride * 2;
     int32_t *out = idx + (int64_t)t * cap;
     int n = 0;
     for (int e = 0; e < E; ++e) {

@@ -56,6 +56,11 @@ def test_sizes(lib):
     # chunks longer than a row tile get several tiles
     B2 = np.array([0, 1000], dtype=np.int32)
     assert dhsa.dhsa_plan_bytes(mk(N_c=1), B2) > 0
+    # row-block form: the plan holds N_r = ceil(L / B_r) lists per head, the workspace S_c of N_r x N_c
+    pr = mk(B_r=100)
+    assert dhsa.dhsa_plan_bytes(pr, B) > 0
+    assert dhsa.dhsa_workspace_bytes(pr, B) >= 8 * (4 * 10 * 128 + 2 * 10 * 128 + 4 * 10 * 10)
+    assert dhsa.dhsa_workspace_bytes(mk(B_r=10), B) >= 8 * (4 * 100 * 128 + 2 * 10 * 128 + 4 * 100 * 10)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -69,6 +74,7 @@ def test_sizes(lib):
     (dict(scale=-1.0), 2),
     (dict(q_stride_l=100), 2),   # row stride shorter than D
     (dict(q_stride_l=132), 9),   # 264-byte rows break 16-byte alignment
+    (dict(B_r=-1), 2),           # row-block size below 0
 ])
 def test_bad_problems_are_rejected_on_the_host(lib, kw, code):
     p = mk(**kw)
