@@ -23,11 +23,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
-# HBM bytes of the attention step on c3 (both k_attn_mfma launches), from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/attn_mfma_c3_counters.md (counter KiB x the copy-kernel factors 2.0 / 1.0 of
-# profiles/counter_calibration.md).  The K/V gather asks the L2 for 220 GB; 41 % of it hits.
-MEASURED_TRAFFIC_C3 = {"fetch_bytes": 1.32e11, "write_bytes": 1.074e9}
+# HBM bytes of the attention step on c3 (all k_attn_mfma launches of one step), from the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_mfma_c3_counters.md and
+# profiles/attn_mfma_c3_blocks_counters.md (counter KiB x the copy-kernel factors 2.0 / 1.0 of
+# profiles/counter_calibration.md), keyed by B_r.  The K/V gather asks the L2 for 220 GB (row form) /
+# 146 GB (row blocks of 128); 46 % / 56 % of the requests hit.
+MEASURED_TRAFFIC_C3 = {0: {"fetch_bytes": 1.189e11, "write_bytes": 1.074e9},
+                       128: {"fetch_bytes": 6.20e10, "write_bytes": 1.074e9}}
 PAPER_CONTEXT = {"what": "paper Tab. 11, DHSA 6.25% @128K, LLaMA-3.1-8B bf16, attention kernel only",
                  "ms_per_layer": 214.5, "hardware": "RTX 3090"}
 
@@ -39,6 +41,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", help="c1..c5 (the metric is quoted on c3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--B_r", type=int, default=0,
+                    help="0 (default, the headline): per-row budgets on the dynamic chunks; > 0: time Alg. 1 as "
+                         "printed with row blocks of this many rows instead")
     ap.add_argument("--no-block-form", action="store_true",
                     help="skip the extra measurement of Alg. 1 as printed (row blocks of 128 rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -92,13 +97,23 @@ def main() -> int:
         ms = e0.elapsed_time(e1) / args.steps
         return ms, float(np.mean([a.elapsed_time(b) for a, b in evs])), wall
 
-    ms_per_step, attn_ms, wall_ms = measure(0)
+    ms_per_step, attn_ms, wall_ms = measure(args.B_r)
     route_ms = ms_per_step - attn_ms
 
-    flops = 4.0 * w.D * w.pairs_per_head() * w.H_q          # selected (row, key) pairs only
+    def listed_pairs(B_r):
+        """(row, key) pairs per head.  Row form: sum_i min(N_b, i+1).  Row-block form: rows x min(N_b, block
+        end) summed over blocks (the pairs the causal mask removes inside a block's own range are not
+        subtracted: under 1 % at these sizes)."""
+        if B_r == 0:
+            return float(w.pairs_per_head())
+        ends = np.minimum((np.arange((w.L + B_r - 1) // B_r) + 1) * B_r, w.L)
+        return float((np.diff(np.r_[0, ends]) * np.minimum(min(w.N_b, w.L), ends)).sum())
+
+    flops = 4.0 * w.D * listed_pairs(args.B_r) * w.H_q      # selected (row, key) pairs only
     achieved = flops / (attn_ms * 1e-3) / 1e12
     out = {
-        "metric": "DHSA prefill ms/layer @128K, 6.25% density; % of MFMA bf16 peak",
+        "metric": "DHSA prefill ms/layer @128K, 6.25% density; % of MFMA bf16 peak"
+                  + (f" [Alg. 1 row blocks, B_r={args.B_r}]" if args.B_r else ""),
         "value": round(ms_per_step, 4), "unit": "ms/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
@@ -109,24 +124,23 @@ def main() -> int:
         "stages_ms": {"route(pool+S_c+select)": round(route_ms, 4), "sparse_attention": round(attn_ms, 4),
                       "host_wall_per_step": round(wall_ms, 4)},
         "pct_of_bf16_mfma_peak": round(100.0 * achieved / PEAK_BF16_TFLOPS, 3),
-        "roofline": {"bound": "mfma", "kernel": "k_attn_mfma (two launches: tiles of > 64 rows, tiles of <= 64 rows)", "achieved": round(achieved, 3),
+        "roofline": {"bound": "mfma",
+                     "kernel": "k_attn_mfma (launches: row tiles of > 64 rows, then row tiles of <= 64 rows)",
+                     "achieved": round(achieved, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 5),
                      "flop_per_launch": flops,
-                     "traffic": (MEASURED_TRAFFIC_C3["fetch_bytes"] + MEASURED_TRAFFIC_C3["write_bytes"]
-                                 if args.workload == "c3" and MEASURED_TRAFFIC_C3["fetch_bytes"] else None),
-                     "traffic_detail": MEASURED_TRAFFIC_C3 if args.workload == "c3" else None},
+                     "traffic": (sum(MEASURED_TRAFFIC_C3[args.B_r].values())
+                                 if args.workload == "c3" and args.B_r in MEASURED_TRAFFIC_C3 else None),
+                     "traffic_detail": (MEASURED_TRAFFIC_C3[args.B_r]
+                                        if args.workload == "c3" and args.B_r in MEASURED_TRAFFIC_C3 else None)},
         "paper_context": PAPER_CONTEXT,
     }
-    if not args.no_block_form:
+    if not args.no_block_form and args.B_r == 0:
         # Alg. 1 as printed on the same tensors: row blocks of B_r = 128 rows, one list of N_b keys per block,
-        # causal mask per token.  Listed (row, key) pairs: sum over blocks of rows x min(N_b, block end);
-        # the pairs the causal mask removes inside a block's own range are not subtracted (< 1 % here).
+        # causal mask per token
         B_r = 128
         ms_b, attn_b, _ = measure(B_r)
-        ends = np.minimum((np.arange((w.L + B_r - 1) // B_r) + 1) * B_r, w.L)
-        rows_b = np.diff(np.r_[0, ends])
-        pairs_b = float((rows_b * np.minimum(min(w.N_b, w.L), ends)).sum())
-        fl_b = 4.0 * w.D * pairs_b * w.H_q
+        fl_b = 4.0 * w.D * listed_pairs(B_r) * w.H_q
         out["alg1_block_form"] = {"B_r": B_r, "ms_per_layer": round(ms_b, 4), "sparse_attention_ms": round(attn_b, 4),
                                   "route_ms": round(ms_b - attn_b, 4), "flop_listed_pairs": fl_b,
                                   "achieved_tflops": round(fl_b / (attn_b * 1e-3) / 1e12, 3),
