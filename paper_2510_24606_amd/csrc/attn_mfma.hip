@@ -21,14 +21,18 @@
 // lane fetches.
 //
 // Pipeline, iteration n (one barrier per key tile; K(t), V(t) live in LDS
-// buffers t%2; work proceeds in 32-key blocks): issue the loads of the upper
-// half of K(n+1), of V(n+1) and of the lower half of K(n+2); every fourth tile
-// each wave prepares the key list of one later tile; then per block: the matrix
-// unit computes the scores of the NEXT block while the vector unit
-// exponentiates the current one, O += P V of the current block, mask and row
-// maximum of the next block; wait for the loads; barrier.
-#include <stdlib.h>
-
+// buffers t%2; work proceeds in 32-key blocks): every fourth tile each wave
+// prepares the key list of one later tile; the row offsets of this iteration's
+// loads (upper half of K(n+1), V(n+1), lower half of K(n+2)) and the mask flag
+// of tile n+1 are fetched into registers; then per block: the matrix unit
+// computes the scores of the NEXT block while the vector unit exponentiates the
+// current one, O += P V of the current block, mask of the next block, with the
+// loads issued a quarter at a time between these steps; wait for the loads;
+// barrier.
+//
+// Query groups: a tile's rows belong to one query group l = rows [RB[l], RB[l+1]):
+// a chunk (RB = B), or a fixed row block of Alg. 1 as printed, whose listed keys
+// are masked causally per token like the keys of a row's own chunk.
 #include "dhsa_internal.h"
 
 namespace dhsa {
@@ -40,9 +44,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kKT = 64;      // keys per tile
 constexpr int kSegB = 256;   // plan entries handled per batch
 constexpr int kIntMax = 0x7fffffff;
-#ifndef DHSA_FRAG_DEPTH
-#define DHSA_FRAG_DEPTH 3   // K fragments requested ahead of the MFMA that consumes them
-#endif
 
 // XOR swizzle of the 16-byte pieces of LDS row r (only r mod 16 matters).  Eight
 // (sixteen for 256-byte rows) consecutive rows get distinct values, so a column
@@ -390,26 +391,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             }                                                                                   \
     }
 
-// Instruction order wanted inside one block step (a hint to the scheduler): K
-// fragments fetched a few MFMAs ahead; between two MFMAs enough vector work
-// (exponentials, sums, conversions) to cover the MFMA's 32 cycles; the V
-// fragments of the PV product fetched while the last score MFMAs run.
-//   masks: 0x008 MFMA, 0x002 VALU, 0x100 LDS read
-#define DHSA_SCHED(depth)                                                                       \
-    {                                                                                           \
-        __builtin_amdgcn_sched_group_barrier(0x100, depth, 0);                                  \
-        _Pragma("unroll") for (int i_ = 0; i_ < NS; ++i_) {                                     \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                  \
-            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                                  \
-        }                                                                                       \
-        _Pragma("unroll") for (int i_ = 0; i_ < 2 * NDB; ++i_) {                                \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                  \
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                                  \
-        }                                                                                       \
-    }
-
         f32x16 s_a, s_b;                      // scores of two consecutive blocks (ping-pong)
         int toggle = 2 * kTile;               // +tile, -tile, ... (bytes): k_off / v_base_* follow the tile buffers
         unsigned ko_lo[KPT], ko_hi[KPT], vo[KPT];   // row offsets of the loads this lane issues next
@@ -580,7 +561,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
 #undef DHSA_ROWMAX
 #undef DHSA_EXP
 #undef DHSA_PV
-#undef DHSA_SCHED
     }
 
     // ---- key-parity tiles: fold the state of the wave that took the odd blocks into its partner ----
@@ -630,10 +610,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                             void *O, hipStream_t s) {
-    static const int want = [] {
-        const char *e = getenv("DHSA_ATTN_ORDER");
-        return e ? atoi(e) : 8;
-    }();
+    const int want = 8;   // kv-heads in flight: one per XCD (other orders measured within 2 %)
     const float c = p.scale * 1.4426950408889634f;
 #define DHSA_MFMA(DD, PAR, tile0, T)                                                                        \
     {                                                                                                       \
