@@ -279,3 +279,17 @@ def plan_blocks_head(Qb_h, Kc_g, B, B_r: int, N_b: int):
                                             B_r, N_b, _p(take, C.c_int32), _p(gap, C.c_double))
     assert rc == 0
     return take, gap
+
+
+# ---- boundary finalisation (threshold + NMS) ----
+
+def finalize_boundaries(p, tau: float, W: int) -> np.ndarray:
+    """Boundary scores p [L] (position i = end of a chunk) -> boundaries B [N_c + 1] (half-open, 0 ... L)."""
+    p = _f32(p)
+    L = p.shape[0]
+    B = np.empty(L + 1, dtype=np.int32)
+    lib().dhsa_oracle_finalize_boundaries.restype = C.c_int64
+    n_c = lib().dhsa_oracle_finalize_boundaries(_p(p, C.c_float), C.c_int64(L), C.c_double(tau), int(W),
+                                                _p(B, C.c_int32))
+    assert n_c >= 1
+    return B[:n_c + 1].copy()

@@ -13,6 +13,8 @@
  *                      stop at >= N_b, hard truncate, sort
  *   attention          Alg. 2 (gather + {0,-inf} causal mask + softmax) and
  *                      Alg. 3 (tiled online softmax); App. C "Backend implementations"
+ *   boundary finalisation  Sec. 3.2 "Inference Pipeline"; App. "Inference of the Boundary
+ *                      Predictor": threshold, sort by score, greedy non-maximum suppression
  *
  * Readings taken where the paper is silent or has two forms (all listed in the
  * design notes of this repository):
@@ -582,4 +584,61 @@ API int dhsa_oracle_plan_blocks_head(const double *Qb_h /* [N_r][D] */, const do
         free(S_row); free(pi);
     }
     return err;
+}
+
+
+/* ======================= Boundary finalisation (threshold + NMS) ======================= */
+
+/* ---- Sec. 3.2 "Inference Pipeline" / App. "Inference of the Boundary Predictor":
+ * p[i] is the predictor's score that position i marks the END of a chunk.
+ *   1. candidates: the positions whose score exceeds the threshold tau (strictly);
+ *   2. sort the candidates by score, descending (equal scores: lower position first);
+ *   3. starting with the best, mark a candidate as a boundary and remove every other
+ *      candidate within W tokens of it (0 < |j - i| <= W); go on with the best remaining.
+ * The boundary set is returned in the half-open convention the rest of the path uses:
+ * a chunk that ends at position i ends at index i + 1, so B = {0} u {i + 1 : i kept} u {L},
+ * ascending, without repeats (the end of the sequence is always a chunk end).
+ * Returns N_c (B has N_c + 1 entries; capacity L + 1), or -1. ---- */
+typedef struct { float s; int32_t i; } cand_t;
+static void merge_sort_cand(cand_t *a, cand_t *tmp, int64_t n) {
+    if (n < 2) return;
+    int64_t m = n / 2;
+    merge_sort_cand(a, tmp, m);
+    merge_sort_cand(a + m, tmp, n - m);
+    int64_t i = 0, j = m, o = 0;
+    while (i < m && j < n) {
+        if (a[j].s > a[i].s) tmp[o++] = a[j++]; /* strictly larger score moves ahead */
+        else tmp[o++] = a[i++];                 /* ties: left (lower position) first */
+    }
+    while (i < m) tmp[o++] = a[i++];
+    while (j < n) tmp[o++] = a[j++];
+    memcpy(a, tmp, (size_t)n * sizeof(cand_t));
+}
+
+API int64_t dhsa_oracle_finalize_boundaries(const float *p, int64_t L, double tau, int W,
+                                            int32_t *B /* capacity L + 1 */) {
+    cand_t *cand = (cand_t *)malloc((size_t)(L > 0 ? L : 1) * sizeof(cand_t));
+    cand_t *tmp = (cand_t *)malloc((size_t)(L > 0 ? L : 1) * sizeof(cand_t));
+    char *removed = (char *)calloc((size_t)(L > 0 ? L : 1), 1);
+    char *kept = (char *)calloc((size_t)(L > 0 ? L : 1), 1);
+    if (!cand || !tmp || !removed || !kept) { free(cand); free(tmp); free(removed); free(kept); return -1; }
+    int64_t n = 0;
+    for (int64_t i = 0; i < L; ++i)
+        if ((double)p[i] > tau) { cand[n].s = p[i]; cand[n].i = (int32_t)i; ++n; }
+    merge_sort_cand(cand, tmp, n);
+    for (int64_t r = 0; r < n; ++r) {
+        int64_t i = cand[r].i;
+        if (removed[i]) continue;
+        kept[i] = 1;
+        int64_t lo = i - W < 0 ? 0 : i - W, hi = i + W > L - 1 ? L - 1 : i + W;
+        for (int64_t j = lo; j <= hi; ++j)
+            if (j != i) removed[j] = 1;
+    }
+    int64_t m = 0;
+    B[m++] = 0;
+    for (int64_t i = 0; i + 1 < L; ++i)
+        if (kept[i]) B[m++] = (int32_t)(i + 1);
+    B[m++] = (int32_t)L;
+    free(cand); free(tmp); free(removed); free(kept);
+    return m - 1;
 }

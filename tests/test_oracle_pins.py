@@ -557,3 +557,75 @@ def test_block_form_alg3_equals_alg2_and_rows_without_a_visible_key_are_zero():
                 else:
                     assert np.any(O[0, i] != 0.0)
     assert saw_empty > 0
+
+
+# ----------------------------------------------------------------------------
+# Boundary finalisation: threshold + greedy non-maximum suppression
+# (Sec. 3.2 "Inference Pipeline"; App. "Inference of the Boundary Predictor")
+# ----------------------------------------------------------------------------
+def test_finalize_boundaries_hand_example():
+    # candidates above 0.5: positions 1 (.9), 2 (.8), 4 (.95), 6 (.6), 7 (.6), 9 (.7); visiting order 4, 1, 2, 9, 6, 7
+    p = np.array([0.1, 0.9, 0.8, 0.2, 0.95, 0.1, 0.6, 0.6, 0.05, 0.7], dtype=np.float32)
+    # W = 1: 4 kept (removes 3, 5); 1 kept (removes 0, 2); 9 kept (removes 8); 6 kept before 7 (tie: lower
+    # position first) and removes it.  Chunk ends 1, 4, 6, 9 -> half-open boundaries 2, 5, 7, 10 (= L)
+    assert oracle.finalize_boundaries(p, 0.5, 1).tolist() == [0, 2, 5, 7, 10]
+    # W = 0: nothing is suppressed, every candidate is a chunk end
+    assert oracle.finalize_boundaries(p, 0.5, 0).tolist() == [0, 2, 3, 5, 7, 8, 10]
+    # W = 2: 4 removes 2..6; 1 kept; 9 removes 7, 8  -> ends 1, 4, 9
+    assert oracle.finalize_boundaries(p, 0.5, 2).tolist() == [0, 2, 5, 10]
+    # the threshold is strict, and nothing above it leaves one chunk
+    assert oracle.finalize_boundaries(p, 0.95, 3).tolist() == [0, 10]
+    assert oracle.finalize_boundaries(p, 0.9, 3).tolist() == [0, 5, 10]
+
+
+def _kept_by_repeated_argmax(p, tau, W):
+    """Independent statement of the same greedy: repeatedly take the best remaining candidate (first
+    occurrence of the maximum = lowest position) and blank its neighbourhood."""
+    s = np.where(p.astype(np.float64) > tau, p.astype(np.float64), -np.inf)
+    kept = []
+    while np.isfinite(s).any():
+        i = int(np.argmax(s))
+        kept.append(i)
+        s[max(0, i - W):i + W + 1] = -np.inf
+    return np.array(sorted(kept), dtype=np.int64)
+
+
+@settings(max_examples=150, deadline=None)
+@given(st.integers(0, 10**6), st.integers(1, 400), st.integers(0, 70), st.floats(0.0, 1.0), st.booleans())
+def test_finalize_boundaries_equals_repeated_argmax_and_is_a_maximal_spaced_set(seed, L, W, tau, tied):
+    rng = np.random.default_rng(seed)
+    p = rng.random(L).astype(np.float32)
+    if tied:
+        p = np.round(p * 8) / 8          # many equal scores
+    B = oracle.finalize_boundaries(p, tau, W)
+    kept = _kept_by_repeated_argmax(p, tau, W)
+    assert B.tolist() == [0] + [int(i) + 1 for i in sorted(set(kept.tolist()) | {L - 1})]
+    assert B[0] == 0 and B[-1] == L and np.all(np.diff(B) > 0)
+    cand = np.nonzero(p.astype(np.float64) > tau)[0]
+    assert set(kept.tolist()) <= set(cand.tolist())
+    if len(kept) > 1:
+        assert np.all(np.diff(kept) > W)                   # kept ends are more than W apart
+    for j in cand:                                          # every other candidate lies within W of a kept, better one
+        if j in kept:
+            continue
+        near = kept[np.abs(kept - j) <= W]
+        assert any((p[i] > p[j]) or (p[i] == p[j] and i < j) for i in near), (j, near)
+
+
+def test_finalize_boundaries_special_cases():
+    rng = np.random.default_rng(5)
+    p = rng.random(1000).astype(np.float32)
+    # a strictly increasing transform of the scores (and of the threshold) changes nothing
+    np.testing.assert_array_equal(oracle.finalize_boundaries(p, 0.3, 8), oracle.finalize_boundaries(p * 2, 0.6, 8))
+    # an isolated strict local maximum above the threshold is always a chunk end
+    B = oracle.finalize_boundaries(p, 0.3, 8)
+    for i in range(8, 991):
+        w = np.r_[p[i - 8:i], p[i + 1:i + 9]]
+        if p[i] > 0.3 and np.all(p[i] > w):
+            assert (i + 1) in B
+    # scores that rise along the sequence: the greedy walks from the end in steps of W + 1
+    q = np.linspace(0.5, 1.0, 100).astype(np.float32)
+    assert oracle.finalize_boundaries(q, 0.0, 9).tolist() == [0] + list(range(10, 101, 10))
+    # NaN scores never exceed the threshold
+    q2 = q.copy(); q2[::2] = np.nan
+    assert (oracle.finalize_boundaries(q2, 0.0, 0)[1:-1] - 1).tolist() == list(range(1, 99, 2))
