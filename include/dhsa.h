@@ -151,6 +151,28 @@ dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void
                          const int32_t *B_host, void *O_dev, void *plan_dev, size_t plan_bytes,
                          void *ws_dev, size_t ws_bytes, void *stream);
 
+/* The step just before the path: boundary scores -> chunk boundaries (Sec. 3.2
+ * "Inference Pipeline"; App. "Inference of the Boundary Predictor").
+ * scores_dev[i], i in [0, L), is the predictor's score that position i marks the
+ * END of a chunk (fp32, device; the predictor network itself is not part of this
+ * library).  Positions whose score does not exceed `threshold` are dropped; the
+ * others are visited by descending score (equal scores: lower position first); a
+ * visited position that has not been removed becomes a chunk end and removes
+ * every other candidate within `window` tokens of it (0 < |j - i| <= window).
+ * Output, in the half-open convention of the rest of the ABI:
+ * B_dev = {0} u {i + 1 : i kept} u {L}, ascending, no repeats (the sequence end is
+ * always a chunk end), N_c + 1 int32 entries, capacity L + 1; *N_c_dev = N_c.
+ * Both are DEVICE memory: copy them to the host after synchronising `stream`
+ * (the other entry points take B as a host array; boundaries are made once per
+ * prompt).  ws_dev: device scratch of dhsa_finalize_boundaries_workspace_bytes(L)
+ * bytes.  Asynchronous like the path itself.  A NaN score never exceeds the
+ * threshold.  Errors: NULL pointers, L outside [1, 2^31), window < 0 or a NaN
+ * threshold (DHSA_ERR_SHAPE), workspace too small. */
+dhsa_status dhsa_finalize_boundaries(const float *scores_dev, int64_t L, float threshold, int32_t window,
+                                     int32_t *B_dev, int32_t *N_c_dev, void *ws_dev, size_t ws_bytes,
+                                     void *stream);
+size_t dhsa_finalize_boundaries_workspace_bytes(int64_t L);
+
 /* ---- inspection hooks (tests, stage-wise parity) ---- */
 
 /* Expand the plan into explicit index sets I_{h,i} (Alg. 1's output) for one

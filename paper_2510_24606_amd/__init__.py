@@ -22,6 +22,7 @@ POS_SHIFT = 28
 
 EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse_prefill", "dhsa_prefill",
            "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
+           "dhsa_finalize_boundaries", "dhsa_finalize_boundaries_workspace_bytes",
            "dhsa_status_string", "dhsa_version"]
 
 
@@ -68,6 +69,10 @@ def lib() -> C.CDLL:
         l.dhsa_mfma_probe.argtypes = [C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
         l.dhsa_mfma_probe.restype = C.c_int
         l.dhsa_mfma_probe_scratch_bytes.argtypes = []; l.dhsa_mfma_probe_scratch_bytes.restype = C.c_size_t
+        l.dhsa_finalize_boundaries.argtypes = [vp, C.c_int64, C.c_float, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+        l.dhsa_finalize_boundaries.restype = C.c_int
+        l.dhsa_finalize_boundaries_workspace_bytes.argtypes = [C.c_int64]
+        l.dhsa_finalize_boundaries_workspace_bytes.restype = C.c_size_t
         l.dhsa_status_string.argtypes = [C.c_int]; l.dhsa_status_string.restype = C.c_char_p
         l.dhsa_version.argtypes = []; l.dhsa_version.restype = C.c_int
         _lib = l
@@ -195,6 +200,21 @@ def dhsa_mfma_probe(random_operands: bool, iters: int = 100000):
     _check(L.dhsa_mfma_probe(int(bool(random_operands)), int(iters), scratch.data_ptr(), n, C.byref(tf), C.byref(mhz),
                              _stream()))
     return tf.value, mhz.value
+
+
+def dhsa_finalize_boundaries(scores, threshold: float, window: int) -> np.ndarray:
+    """Boundary scores [L] (fp32 device tensor; position i = end of a chunk) -> boundaries B as a host
+    int32 array [N_c + 1] (0 ... L).  Synchronises the stream to bring B to the host."""
+    import torch
+    L = int(scores.shape[0])
+    n = int(lib().dhsa_finalize_boundaries_workspace_bytes(L))
+    ws = torch.empty(max(n, 1), dtype=torch.uint8, device=scores.device)
+    B = torch.empty(L + 1, dtype=torch.int32, device=scores.device)
+    N_c = torch.zeros(1, dtype=torch.int32, device=scores.device)
+    _check(lib().dhsa_finalize_boundaries(scores.data_ptr(), L, float(threshold), int(window), B.data_ptr(),
+                                          N_c.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    torch.cuda.synchronize()
+    return B[:int(N_c.item()) + 1].cpu().numpy()
 
 
 def dhsa_version() -> int:

@@ -117,6 +117,20 @@ def test_mfma_probe_rejects_bad_arguments_on_the_host(lib):
     assert lib.dhsa_mfma_probe(0, 100, fake, need - 1, C.byref(tf), None, None) == 6
 
 
+def test_finalize_boundaries_rejects_bad_arguments_on_the_host(lib):
+    import ctypes as C
+    fake = C.c_void_p(256)   # never dereferenced: every call below fails validation first (1 NULL, 2 SHAPE, 6 WORKSPACE)
+    need = lib.dhsa_finalize_boundaries_workspace_bytes(1000)
+    assert need >= 1000 and lib.dhsa_finalize_boundaries_workspace_bytes(0) == 0
+    f = lib.dhsa_finalize_boundaries
+    assert f(None, 1000, 0.5, 8, fake, fake, fake, need, None) == 1
+    assert f(fake, 1000, 0.5, 8, None, fake, fake, need, None) == 1
+    assert f(fake, 0, 0.5, 8, fake, fake, fake, need, None) == 2
+    assert f(fake, 1000, 0.5, -1, fake, fake, fake, need, None) == 2
+    assert f(fake, 1000, float("nan"), 8, fake, fake, fake, need, None) == 2
+    assert f(fake, 1000, 0.5, 8, fake, fake, fake, need - 1, None) == 6
+
+
 def test_no_oracle_in_the_product_path():
     """The product package must not import, load or call the oracle."""
     pkg = os.path.join(ROOT, "paper_2510_24606_amd")
