@@ -77,6 +77,13 @@ typedef enum {
 
 typedef enum { DHSA_F32 = 0, DHSA_BF16 = 1 } dhsa_dtype;
 
+/* Chunk representation.  DHSA_POOL_ROBUST: Sec. 3.3 Eq. 4, sqrt(len)/len * sum (and
+ * sqrt(B_r) * AvgPool for the row blocks of Alg. 1).  DHSA_POOL_MEAN: plain average,
+ * the ablation "without robust chunk representation" (App. D); with fixed-size
+ * chunks on top (uniform boundaries) the method is conventional block-sparse
+ * attention, as that appendix notes. */
+typedef enum { DHSA_POOL_ROBUST = 0, DHSA_POOL_MEAN = 1 } dhsa_pooling;
+
 /* Problem statement of Sec. 3.1 / Alg. 1-3: sequence length L, chunk count N_c
  * (boundaries passed separately), per-row token budget N_b, GQA head counts. */
 typedef struct {
@@ -92,6 +99,7 @@ typedef struct {
     int64_t o_stride_h, o_stride_l;
     int32_t B_r;              /* 0: per-row budgets on the dynamic chunks (steps 1-5 above);
                                  > 0: Alg. 1 as printed with row blocks of B_r rows        */
+    int32_t pooling;          /* dhsa_pooling: how chunks (and row blocks) are represented  */
 } dhsa_problem;
 
 /*

@@ -66,6 +66,17 @@ def pool(X: np.ndarray, B: np.ndarray) -> np.ndarray:
     return out
 
 
+def pool_mean(X: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """Plain average pooling of X [H, L, D] over the chunks (the ablation without Eq. 4's factor)."""
+    X = _f32(X); B = _i32(B)
+    H, L, D = X.shape
+    N_c = B.shape[0] - 1
+    out = np.empty((H, N_c, D), dtype=np.float64)
+    rc = lib().dhsa_oracle_pool_mean(_p(X, C.c_float), H, C.c_int64(L), D, _p(B, C.c_int32), N_c, _p(out, C.c_double))
+    assert rc == 0
+    return out
+
+
 def scores(Qc: np.ndarray, Kc: np.ndarray) -> np.ndarray:
     """S_c[h] = Q_c[h] K_c[h // G]^T, full [H_q, N_c, N_c] (fp64)."""
     Qc = _f64(Qc); Kc = _f64(Kc)
@@ -144,7 +155,7 @@ def chunk_walk(pi: np.ndarray, B: np.ndarray, l: int) -> Tuple[np.ndarray, np.nd
     return before, pos
 
 
-def route_rows(Q, K, B, N_b: int, rows) -> Tuple[np.ndarray, np.ndarray]:
+def route_rows(Q, K, B, N_b: int, rows, pooling: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Index sets of the given rows for every query head: (I [H_q, n, N_b] (-1 padded), cnt [H_q, n])."""
     Q = _f32(Q); K = _f32(K); B = _i32(B)
     rows = np.ascontiguousarray(rows, dtype=np.int64)
@@ -154,13 +165,13 @@ def route_rows(Q, K, B, N_b: int, rows) -> Tuple[np.ndarray, np.ndarray]:
     I = np.empty((H_q, n, N_b), dtype=np.int32)
     cnt = np.empty((H_q, n), dtype=np.int32)
     rc = lib().dhsa_oracle_route_rows(_p(Q, C.c_float), _p(K, C.c_float), H_q, H_kv, C.c_int64(L), D,
-                                      _p(B, C.c_int32), B.shape[0] - 1, N_b, _p(rows, C.c_int64), n,
+                                      _p(B, C.c_int32), B.shape[0] - 1, N_b, int(pooling), _p(rows, C.c_int64), n,
                                       _p(I, C.c_int32), _p(cnt, C.c_int32))
     assert rc == 0
     return I, cnt
 
 
-def prefill_rows(Q, K, V, B, N_b: int, rows, scale: Optional[float] = None):
+def prefill_rows(Q, K, V, B, N_b: int, rows, scale: Optional[float] = None, pooling: int = 0):
     """The whole path on the given rows: (O [H_q, n, D] fp64, I, cnt)."""
     Q = _f32(Q); K = _f32(K); V = _f32(V); B = _i32(B)
     rows = np.ascontiguousarray(rows, dtype=np.int64)
@@ -173,9 +184,9 @@ def prefill_rows(Q, K, V, B, N_b: int, rows, scale: Optional[float] = None):
     I = np.empty((H_q, n, N_b), dtype=np.int32)
     cnt = np.empty((H_q, n), dtype=np.int32)
     rc = lib().dhsa_oracle_prefill_rows(_p(Q, C.c_float), _p(K, C.c_float), _p(V, C.c_float), H_q, H_kv,
-                                        C.c_int64(L), D, _p(B, C.c_int32), B.shape[0] - 1, N_b, C.c_double(scale),
-                                        _p(rows, C.c_int64), n, _p(O, C.c_double), _p(I, C.c_int32),
-                                        _p(cnt, C.c_int32))
+                                        C.c_int64(L), D, _p(B, C.c_int32), B.shape[0] - 1, N_b, int(pooling),
+                                        C.c_double(scale), _p(rows, C.c_int64), n, _p(O, C.c_double),
+                                        _p(I, C.c_int32), _p(cnt, C.c_int32))
     assert rc == 0
     return O, I, cnt
 
@@ -232,7 +243,18 @@ def select_pairs_blocks(Sb_h, B, B_r: int, N_b: int) -> Tuple[np.ndarray, np.nda
     return I, cnt
 
 
-def route_blocks(Q, K, B, B_r: int, N_b: int, blocks) -> Tuple[np.ndarray, np.ndarray]:
+def pool_blocks_mean(X: np.ndarray, B_r: int) -> np.ndarray:
+    """Plain average of every row block of X [H, L, D] -> [H, N_r, D] (fp64)."""
+    X = _f32(X)
+    H, L, D = X.shape
+    N_r = (L + B_r - 1) // B_r
+    out = np.empty((H, N_r, D), dtype=np.float64)
+    rc = lib().dhsa_oracle_pool_blocks_mean(_p(X, C.c_float), H, C.c_int64(L), D, B_r, _p(out, C.c_double))
+    assert rc == 0
+    return out
+
+
+def route_blocks(Q, K, B, B_r: int, N_b: int, blocks, pooling: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Index lists of the given row blocks for every query head: (I [H_q, n, N_b] (-1 padded), cnt [H_q, n])."""
     Q = _f32(Q); K = _f32(K); B = _i32(B)
     blocks = np.ascontiguousarray(blocks, dtype=np.int64)
@@ -242,13 +264,13 @@ def route_blocks(Q, K, B, B_r: int, N_b: int, blocks) -> Tuple[np.ndarray, np.nd
     I = np.empty((H_q, n, N_b), dtype=np.int32)
     cnt = np.empty((H_q, n), dtype=np.int32)
     rc = lib().dhsa_oracle_route_blocks(_p(Q, C.c_float), _p(K, C.c_float), H_q, H_kv, C.c_int64(L), D,
-                                        _p(B, C.c_int32), B.shape[0] - 1, B_r, N_b, _p(blocks, C.c_int64), n,
-                                        _p(I, C.c_int32), _p(cnt, C.c_int32))
+                                        _p(B, C.c_int32), B.shape[0] - 1, B_r, N_b, int(pooling),
+                                        _p(blocks, C.c_int64), n, _p(I, C.c_int32), _p(cnt, C.c_int32))
     assert rc == 0
     return I, cnt
 
 
-def prefill_rows_blocks(Q, K, V, B, B_r: int, N_b: int, rows, scale: Optional[float] = None):
+def prefill_rows_blocks(Q, K, V, B, B_r: int, N_b: int, rows, scale: Optional[float] = None, pooling: int = 0):
     """The block-form path on the given rows: (O [H_q, n, D] fp64, I of each row's block, cnt)."""
     Q = _f32(Q); K = _f32(K); V = _f32(V); B = _i32(B)
     rows = np.ascontiguousarray(rows, dtype=np.int64)
@@ -262,7 +284,7 @@ def prefill_rows_blocks(Q, K, V, B, B_r: int, N_b: int, rows, scale: Optional[fl
     cnt = np.empty((H_q, n), dtype=np.int32)
     rc = lib().dhsa_oracle_prefill_rows_blocks(_p(Q, C.c_float), _p(K, C.c_float), _p(V, C.c_float), H_q, H_kv,
                                                C.c_int64(L), D, _p(B, C.c_int32), B.shape[0] - 1, B_r, N_b,
-                                               C.c_double(scale), _p(rows, C.c_int64), n, _p(O, C.c_double),
+                                               int(pooling), C.c_double(scale), _p(rows, C.c_int64), n, _p(O, C.c_double),
                                                _p(I, C.c_int32), _p(cnt, C.c_int32))
     assert rc == 0
     return O, I, cnt

@@ -75,6 +75,31 @@ API int dhsa_oracle_pool(const float *X, int H, int64_t L, int D, const int32_t 
     return 0;
 }
 
+/* ---- The ablation "without robust chunk representation" (App. D): plain average
+ * pooling, x_{C_k} = (1 / len_k) * sum of the chunk's vectors. ---- */
+API int dhsa_oracle_pool_mean(const float *X, int H, int64_t L, int D, const int32_t *B, int N_c,
+                              double *Xc /* [H][N_c][D] */) {
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int h = 0; h < H; ++h) {
+        for (int k = 0; k < N_c; ++k) {
+            double len = (double)(B[k + 1] - B[k]);
+            for (int d = 0; d < D; ++d) {
+                double sum = 0.0;
+                for (int64_t i = B[k]; i < B[k + 1]; ++i)
+                    sum += (double)X[((int64_t)h * L + i) * D + d];
+                Xc[((int64_t)h * N_c + k) * D + d] = sum / len;
+            }
+        }
+    }
+    return 0;
+}
+
+/* pooling = 0: Eq. 4; 1: plain average (the ablation) */
+static int pool_by_mode(int pooling, const float *X, int H, int64_t L, int D, const int32_t *B, int N_c,
+                        double *Xc) {
+    return pooling ? dhsa_oracle_pool_mean(X, H, L, D, B, N_c, Xc) : dhsa_oracle_pool(X, H, L, D, B, N_c, Xc);
+}
+
 /* ---- Sec. 3.3: (S_c)_{l,k} = < q_{C_l}, k_{C_k} >, one row l, every key chunk k ---- */
 API int dhsa_oracle_score_row(const double *qc /* [D] */, const double *Kc /* [N_c][D] */, int N_c,
                               int D, double *S_row /* [N_c] */) {
@@ -305,15 +330,15 @@ static int chunk_of_row(const int32_t *B, int N_c, int64_t i) {
  * q_max = i + 1 and the scores of row i's chunk.  Optionally also the per-rank
  * scores are not returned; only index sets. */
 API int dhsa_oracle_route_rows(const float *Q, const float *K, int H_q, int H_kv, int64_t L, int D,
-                               const int32_t *B, int N_c, int N_b, const int64_t *rows, int n_rows,
+                               const int32_t *B, int N_c, int N_b, int pooling, const int64_t *rows, int n_rows,
                                int32_t *I_out /* [H_q][n_rows][N_b], -1 padded */,
                                int32_t *cnt_out /* [H_q][n_rows] */) {
     int G = H_q / H_kv;
     double *Qc = (double *)malloc((size_t)H_q * N_c * D * sizeof(double));
     double *Kc = (double *)malloc((size_t)H_kv * N_c * D * sizeof(double));
     if (!Qc || !Kc) return 1;
-    dhsa_oracle_pool(Q, H_q, L, D, B, N_c, Qc);
-    dhsa_oracle_pool(K, H_kv, L, D, B, N_c, Kc);
+    pool_by_mode(pooling, Q, H_q, L, D, B, N_c, Qc);
+    pool_by_mode(pooling, K, H_kv, L, D, B, N_c, Kc);
     int err = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int h = 0; h < H_q; ++h)
@@ -338,11 +363,11 @@ API int dhsa_oracle_route_rows(const float *Q, const float *K, int H_q, int H_kv
 
 /* The whole path for a list of rows: route (above), then Alg. 2 per row. */
 API int dhsa_oracle_prefill_rows(const float *Q, const float *K, const float *V, int H_q, int H_kv,
-                                 int64_t L, int D, const int32_t *B, int N_c, int N_b, double scale,
+                                 int64_t L, int D, const int32_t *B, int N_c, int N_b, int pooling, double scale,
                                  const int64_t *rows, int n_rows, double *O_out /* [H_q][n_rows][D] */,
                                  int32_t *I_out /* [H_q][n_rows][N_b] */, int32_t *cnt_out) {
     int G = H_q / H_kv;
-    int err = dhsa_oracle_route_rows(Q, K, H_q, H_kv, L, D, B, N_c, N_b, rows, n_rows, I_out, cnt_out);
+    int err = dhsa_oracle_route_rows(Q, K, H_q, H_kv, L, D, B, N_c, N_b, pooling, rows, n_rows, I_out, cnt_out);
     if (err) return err;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int h = 0; h < H_q; ++h)
@@ -436,6 +461,24 @@ API int dhsa_oracle_pool_blocks(const float *X, int H, int64_t L, int D, int B_r
     return 0;
 }
 
+/* Plain average of a row block (the ablation without the sqrt(B_r) factor of the robust representation). */
+API int dhsa_oracle_pool_blocks_mean(const float *X, int H, int64_t L, int D, int B_r,
+                                     double *Xq /* [H][N_r][D] */) {
+    int64_t N_r = (L + B_r - 1) / B_r;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int h = 0; h < H; ++h) {
+        for (int64_t i = 0; i < N_r; ++i) {
+            int64_t q_s = i * B_r, q_e = (i + 1) * B_r < L ? (i + 1) * B_r : L;
+            for (int d = 0; d < D; ++d) {
+                double sum = 0.0;
+                for (int64_t r = q_s; r < q_e; ++r) sum += (double)X[((int64_t)h * L + r) * D + d];
+                Xq[((int64_t)h * N_r + i) * D + d] = sum / (double)(q_e - q_s);
+            }
+        }
+    }
+    return 0;
+}
+
 /* ---- Alg. 1 for one row block i of one head: S_c[i, :] over ALL key chunks,
  * Argsort (stable, descending), walk with q_max = min((i+1) B_r, L).  Returns |I_i|. ---- */
 API int dhsa_oracle_select_block(const double *q_i /* [D] */, const double *Kc_g /* [N_c][D] */,
@@ -485,7 +528,7 @@ API int dhsa_oracle_select_pairs_blocks(const double *Sb_h /* [N_r][N_c] */, con
 
 /* Index lists of a list of row blocks, every query head (GQA as above). */
 API int dhsa_oracle_route_blocks(const float *Q, const float *K, int H_q, int H_kv, int64_t L, int D,
-                                 const int32_t *B, int N_c, int B_r, int N_b, const int64_t *blocks,
+                                 const int32_t *B, int N_c, int B_r, int N_b, int pooling, const int64_t *blocks,
                                  int n_blocks, int32_t *I_out /* [H_q][n_blocks][N_b], -1 padded */,
                                  int32_t *cnt_out /* [H_q][n_blocks] */) {
     int G = H_q / H_kv;
@@ -493,8 +536,9 @@ API int dhsa_oracle_route_blocks(const float *Q, const float *K, int H_q, int H_
     double *Qb = (double *)malloc((size_t)H_q * N_r * D * sizeof(double));
     double *Kc = (double *)malloc((size_t)H_kv * N_c * D * sizeof(double));
     if (!Qb || !Kc) return 1;
-    dhsa_oracle_pool_blocks(Q, H_q, L, D, B_r, Qb);
-    dhsa_oracle_pool(K, H_kv, L, D, B, N_c, Kc);
+    if (pooling) dhsa_oracle_pool_blocks_mean(Q, H_q, L, D, B_r, Qb);
+    else dhsa_oracle_pool_blocks(Q, H_q, L, D, B_r, Qb);
+    pool_by_mode(pooling, K, H_kv, L, D, B, N_c, Kc);
     int err = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int h = 0; h < H_q; ++h)
@@ -516,7 +560,7 @@ API int dhsa_oracle_route_blocks(const float *Q, const float *K, int H_q, int H_
  * block (Alg. 1), then Alg. 2 for the row with its causal mask. */
 API int dhsa_oracle_prefill_rows_blocks(const float *Q, const float *K, const float *V, int H_q, int H_kv,
                                         int64_t L, int D, const int32_t *B, int N_c, int B_r, int N_b,
-                                        double scale, const int64_t *rows, int n_rows,
+                                        int pooling, double scale, const int64_t *rows, int n_rows,
                                         double *O_out /* [H_q][n_rows][D] */,
                                         int32_t *I_out /* [H_q][n_rows][N_b]: the list of the row's block */,
                                         int32_t *cnt_out) {
@@ -524,7 +568,8 @@ API int dhsa_oracle_prefill_rows_blocks(const float *Q, const float *K, const fl
     int64_t *blocks = (int64_t *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int64_t));
     if (!blocks) return 1;
     for (int t = 0; t < n_rows; ++t) blocks[t] = rows[t] / B_r;
-    int err = dhsa_oracle_route_blocks(Q, K, H_q, H_kv, L, D, B, N_c, B_r, N_b, blocks, n_rows, I_out, cnt_out);
+    int err = dhsa_oracle_route_blocks(Q, K, H_q, H_kv, L, D, B, N_c, B_r, N_b, pooling, blocks, n_rows, I_out,
+                                       cnt_out);
     free(blocks);
     if (err) return err;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdhsa.so")
 
 DHSA_F32, DHSA_BF16 = 0, 1
+DHSA_POOL_ROBUST, DHSA_POOL_MEAN = 0, 1
 PLAN_MAGIC = 0x41534844
 POS_SHIFT = 28
 
@@ -33,7 +34,7 @@ class dhsa_problem(C.Structure):
                 ("k_stride_h", C.c_int64), ("k_stride_l", C.c_int64),
                 ("v_stride_h", C.c_int64), ("v_stride_l", C.c_int64),
                 ("o_stride_h", C.c_int64), ("o_stride_l", C.c_int64),
-                ("B_r", C.c_int32)]
+                ("B_r", C.c_int32), ("pooling", C.c_int32)]
 
 
 class DhsaError(RuntimeError):
@@ -97,7 +98,7 @@ def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
-def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0) -> dhsa_problem:
+def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0, pooling: int = 0) -> dhsa_problem:
     """Describe Q [H_q, L, D] and K [H_kv, L, D] (torch tensors, last dim contiguous).
     B_r > 0 selects Alg. 1 as printed (row blocks of B_r rows, one index list per block)."""
     import torch
@@ -106,7 +107,7 @@ def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0) -> dhsa_problem
     dt = {torch.float32: DHSA_F32, torch.bfloat16: DHSA_BF16}.get(Q.dtype, -1)
     return dhsa_problem(L=L, H_q=H_q, H_kv=H_kv, D=D, N_c=len(B) - 1, N_b=N_b, dtype=dt, scale=scale,
                         q_stride_h=Q.stride(0), q_stride_l=Q.stride(1),
-                        k_stride_h=K.stride(0), k_stride_l=K.stride(1), B_r=B_r)
+                        k_stride_h=K.stride(0), k_stride_l=K.stride(1), B_r=B_r, pooling=pooling)
 
 
 def dhsa_plan_bytes(prob: dhsa_problem, B) -> int:

@@ -24,6 +24,7 @@ dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
     if (in->N_c < 1 || in->N_c > kMaxChunks || in->N_c > in->L) return DHSA_ERR_SHAPE;
     if (in->N_b < 1) return DHSA_ERR_BUDGET;
     if (in->B_r < 0) return DHSA_ERR_SHAPE;
+    if (in->pooling != DHSA_POOL_ROBUST && in->pooling != DHSA_POOL_MEAN) return DHSA_ERR_SHAPE;
     // row-block form: N_r = ceil(L / B_r) query groups, one workgroup each in the ranking kernel
     if (in->B_r > 0 && (in->L + in->B_r - 1) / in->B_r > (int64_t)1 << 20) return DHSA_ERR_SHAPE;
     if (!(in->scale >= 0.f) || !isfinite(in->scale)) return DHSA_ERR_SHAPE;
@@ -33,6 +34,7 @@ dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
     p->L = in->L; p->H_q = in->H_q; p->H_kv = in->H_kv; p->G = in->H_q / in->H_kv; p->D = in->D;
     p->N_c = in->N_c;
     p->B_r = in->B_r;
+    p->pooling = in->pooling;
     p->N_q = in->B_r > 0 ? (int)((in->L + in->B_r - 1) / in->B_r) : in->N_c;
     p->N_b = (int)std::min<int64_t>(in->N_b, in->L);
     p->dtype = in->dtype;

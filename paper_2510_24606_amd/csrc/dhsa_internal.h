@@ -18,6 +18,7 @@ struct Prob {
     int64_t L;
     int H_q, H_kv, G, D, N_c, N_b;  // N_b already clamped to L
     int B_r, N_q;                   // row-block size (0 = query groups are the chunks), query groups
+    int pooling;                    // dhsa_pooling
     int dtype;
     float scale;
     int64_t qs_h, qs_l, ks_h, ks_l, vs_h, vs_l, os_h, os_l;

@@ -137,8 +137,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *__restrict__ K,
                                               const int32_t *__restrict__ B, const int32_t *__restrict__ RB,
                                               double *__restrict__ Qc, double *__restrict__ Kc, int H_q, int N_c,
-                                              int N_q, int B_r, int64_t qs_h, int64_t qs_l, int64_t ks_h,
-                                              int64_t ks_l) {
+                                              int N_q, int B_r, int pooling, int64_t qs_h, int64_t qs_l,
+                                              int64_t ks_h, int64_t ks_l) {
     constexpr int EPT = Elem<T>::kPer16;   // elements per thread per row
     constexpr int TPR = D / EPT;           // threads per row
     constexpr int RG = 256 / TPR;          // rows in flight
@@ -175,7 +175,9 @@ __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *
 #pragma unroll 4
         for (int r = 0; r < RG; ++r) sum += s_sum[r][tid];
         const double len = (double)(b1 - b0);
-        Xc[tid] = (is_q && B_r > 0) ? sqrt((double)B_r) * (sum / len) : (sqrt(len) / len) * sum;
+        Xc[tid] = pooling == DHSA_POOL_MEAN ? sum / len                                  // plain average (ablation)
+                  : (is_q && B_r > 0)      ? sqrt((double)B_r) * (sum / len)            // Alg. 1 row blocks
+                                           : (sqrt(len) / len) * sum;                   // Eq. 4
     }
 }
 
@@ -184,7 +186,7 @@ hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_
     dim3 grid(p.N_q > p.N_c ? p.N_q : p.N_c, p.H_q + p.H_kv), block(256);
 #define DHSA_POOL(T, DD)                                                                                  \
     hipLaunchKernelGGL((k_pool<T, DD>), grid, block, 0, s, (const T *)Q, (const T *)K, B_dev, RB_dev, Qc, \
-                       Kc, p.H_q, p.N_c, p.N_q, p.B_r, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
+                       Kc, p.H_q, p.N_c, p.N_q, p.B_r, p.pooling, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
     if (p.dtype == DHSA_F32) {
         if (p.D == 64) DHSA_POOL(float, 64); else DHSA_POOL(float, 128);
     } else {

@@ -75,6 +75,7 @@ def test_sizes(lib):
     (dict(q_stride_l=100), 2),   # row stride shorter than D
     (dict(q_stride_l=132), 9),   # 264-byte rows break 16-byte alignment
     (dict(B_r=-1), 2),           # row-block size below 0
+    (dict(pooling=2), 2),        # unknown chunk representation
 ])
 def test_bad_problems_are_rejected_on_the_host(lib, kw, code):
     p = mk(**kw)

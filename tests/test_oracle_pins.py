@@ -629,3 +629,58 @@ def test_finalize_boundaries_special_cases():
     # NaN scores never exceed the threshold
     q2 = q.copy(); q2[::2] = np.nan
     assert (oracle.finalize_boundaries(q2, 0.0, 0)[1:-1] - 1).tolist() == list(range(1, 99, 2))
+
+
+# ----------------------------------------------------------------------------
+# The ablation "without robust chunk representation": plain average pooling (App. D)
+# ----------------------------------------------------------------------------
+def test_mean_pooling_closed_form_and_its_relation_to_eq4():
+    rng = np.random.default_rng(23)
+    L, D = 90, 6
+    B = rand_boundaries(rng, L, 1, 11)
+    X = rng.standard_normal((2, L, D)).astype(np.float32)
+    lens = np.diff(B).astype(np.float64)
+    want = np.add.reduceat(X.astype(np.float64), B[:-1], axis=1) / lens[None, :, None]
+    np.testing.assert_allclose(oracle.pool_mean(X, B), want, rtol=1e-14, atol=1e-15)
+    # Eq. 4 is sqrt(len) times the plain average, so S_c(mean)[l, k] = S_c(Eq. 4)[l, k] / sqrt(len_l len_k)
+    np.testing.assert_allclose(oracle.pool(X, B), want * np.sqrt(lens)[None, :, None], rtol=1e-14, atol=1e-15)
+    # row blocks: the plain average drops the sqrt(B_r) factor
+    np.testing.assert_allclose(oracle.pool_blocks_mean(X, 7) * math.sqrt(7.0), oracle.pool_blocks(X, 7),
+                                rtol=1e-14, atol=1e-15)
+
+
+def test_mean_pooling_selects_like_eq4_on_equal_chunks_and_differently_on_unequal_ones():
+    rng = np.random.default_rng(29)
+    H_q, H_kv, D = 2, 1, 8
+    # equal chunk lengths: the two representations differ by one common factor, rankings and sets agree (App. D)
+    L = 96
+    B = np.arange(0, L + 1, 8, dtype=np.int32)
+    Q = rng.standard_normal((H_q, L, D)).astype(np.float32)
+    K = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    V = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    rows = np.arange(L)
+    for N_b in (3, 20):
+        I0, c0 = oracle.route_rows(Q, K, B, N_b, rows, pooling=0)
+        I1, c1 = oracle.route_rows(Q, K, B, N_b, rows, pooling=1)
+        np.testing.assert_array_equal(I0, I1)
+        np.testing.assert_array_equal(c0, c1)
+        Ib0, _ = oracle.route_blocks(Q, K, B, 16, N_b, np.arange(6), pooling=0)
+        Ib1, _ = oracle.route_blocks(Q, K, B, 16, N_b, np.arange(6), pooling=1)
+        np.testing.assert_array_equal(Ib0, Ib1)
+    # unequal lengths: the mean favours short chunks less than Eq. 4 favours long ones -- the sets differ somewhere,
+    # and the mean-pooled sets are exactly the walk over rankings of the mean-pooled scores
+    B2 = rand_boundaries(rng, L, 1, 20)
+    I0, _ = oracle.route_rows(Q, K, B2, 10, rows, pooling=0)
+    I1, c1 = oracle.route_rows(Q, K, B2, 10, rows, pooling=1)
+    assert (I0 != I1).any()
+    Qm, Km = oracle.pool_mean(Q, B2), oracle.pool_mean(K, B2)
+    Sm = oracle.scores(Qm, Km)
+    for h in range(H_q):
+        for i in rows:
+            l = int(np.searchsorted(B2, i, side="right") - 1)
+            want = oracle.select(oracle.rank(Sm[h, l]), B2, i + 1, 10)
+            assert I1[h, i, :c1[h, i]].tolist() == want.tolist()
+    O1, _, _ = oracle.prefill_rows(Q, K, V, B2, 10, rows, pooling=1)
+    for i in (0, 17, 95):
+        np.testing.assert_allclose(O1[1, i], oracle.attend_row(Q[1, i], K[0], V[0], I1[1, i, :c1[1, i]], i, 1 / math.sqrt(D)),
+                                   rtol=1e-13, atol=1e-14)
