@@ -315,3 +315,29 @@ def finalize_boundaries(p, tau: float, W: int) -> np.ndarray:
                                                 _p(B, C.c_int32))
     assert n_c >= 1
     return B[:n_c + 1].copy()
+
+
+# ---- recall against exact top-k attention ----
+
+def recall_row(q, Kg, i: int, I_hat, k_top: int) -> Tuple[int, int]:
+    """(|I* n I_hat|, |I*|) for one row: I* = the min(k_top, i+1) keys j <= i with the largest logits."""
+    q = _f32(q); Kg = _f32(Kg); I_hat = _i32(I_hat)
+    hits, size = C.c_int32(0), C.c_int32(0)
+    rc = lib().dhsa_oracle_recall_row(_p(q, C.c_float), _p(Kg, C.c_float), C.c_int64(i), q.shape[0],
+                                      _p(I_hat, C.c_int32), I_hat.shape[0], int(k_top), C.byref(hits), C.byref(size))
+    assert rc == 0
+    return hits.value, size.value
+
+
+def recall_rows(Q, K, B, N_b: int, head: int, rows, B_r: int = 0, pooling: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Recall counts of the routed sets of `rows` of one query head: (hits [n], size [n])."""
+    Q = _f32(Q); K = _f32(K); B = _i32(B)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    H_q, L, D = Q.shape
+    n = rows.shape[0]
+    hits = np.empty(n, dtype=np.int32); size = np.empty(n, dtype=np.int32)
+    rc = lib().dhsa_oracle_recall_rows(_p(Q, C.c_float), _p(K, C.c_float), H_q, K.shape[0], C.c_int64(L), D,
+                                       _p(B, C.c_int32), B.shape[0] - 1, int(B_r), int(N_b), int(pooling), int(head),
+                                       _p(rows, C.c_int64), n, _p(hits, C.c_int32), _p(size, C.c_int32))
+    assert rc == 0
+    return hits, size

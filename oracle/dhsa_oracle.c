@@ -15,6 +15,8 @@
  *                      Alg. 3 (tiled online softmax); App. C "Backend implementations"
  *   boundary finalisation  Sec. 3.2 "Inference Pipeline"; App. "Inference of the Boundary
  *                      Predictor": threshold, sort by score, greedy non-maximum suppression
+ *   recall diagnostic  App. "Theoretical Analysis", Setup and Notation: per-row recall of a
+ *                      selected set against the top-k keys by attention score
  *
  * Readings taken where the paper is silent or has two forms (all listed in the
  * design notes of this repository):
@@ -686,4 +688,78 @@ API int64_t dhsa_oracle_finalize_boundaries(const float *p, int64_t L, double ta
     B[m++] = (int32_t)L;
     free(cand); free(tmp); free(removed); free(kept);
     return m - 1;
+}
+
+
+/* ======================= Recall against exact top-k attention ======================= */
+
+/* ---- App. "Theoretical Analysis" (Setup and Notation), per-row recall:
+ * I*_i = the k keys j <= i with the largest attention scores a_ij (a_ij = exp of
+ * the logit, so: the largest logits q_i . k_j; equal logits -> lower index),
+ * k = min(k_top, i + 1); Recall_i = |I*_i n I_hat_i| / |I*_i| for a selected set
+ * I_hat_i.  Returns |I*_i n I_hat_i| in *hits and |I*_i| in *size.  Logits are
+ * summed in fp64 in the order d = 0, 1, ...: the products of the stored values
+ * are exact in fp64, so this is the value any fp64 evaluation in that order has. ---- */
+API int dhsa_oracle_recall_row(const float *q /* [D] */, const float *Kg /* [L][D] */, int64_t i, int D,
+                               const int32_t *I_hat, int cnt, int k_top, int32_t *hits, int32_t *size) {
+    int64_t n = i + 1;
+    pair_t *row = (pair_t *)malloc((size_t)n * sizeof(pair_t));
+    char *in_top = (char *)calloc((size_t)n, 1);
+    if (!row || !in_top) { free(row); free(in_top); return 1; }
+    for (int64_t j = 0; j < n; ++j) {
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d) acc += (double)q[d] * (double)Kg[j * D + d];
+        row[j].s = acc;
+        row[j].j = (int32_t)j;
+    }
+    qsort(row, (size_t)n, sizeof(pair_t), cmp_pair);   /* logit descending, equal logits by lower index */
+    int64_t k = k_top < n ? k_top : n;
+    for (int64_t t = 0; t < k; ++t) in_top[row[t].j] = 1;
+    int32_t h = 0;
+    for (int v = 0; v < cnt; ++v)
+        if (I_hat[v] >= 0 && I_hat[v] < n && in_top[I_hat[v]]) ++h;
+    *hits = h;
+    *size = (int32_t)k;
+    free(row); free(in_top);
+    return 0;
+}
+
+/* Recall of the routed sets of a list of rows of one query head (row form: the row's
+ * own set; row-block form, B_r > 0: the keys of its block's list at or below the row). */
+API int dhsa_oracle_recall_rows(const float *Q, const float *K, int H_q, int H_kv, int64_t L, int D,
+                                const int32_t *B, int N_c, int B_r, int N_b, int pooling, int head,
+                                const int64_t *rows, int n_rows, int32_t *hits /* [n_rows] */,
+                                int32_t *size /* [n_rows] */) {
+    int G = H_q / H_kv;
+    int32_t *I = (int32_t *)malloc((size_t)H_q * (size_t)(n_rows > 0 ? n_rows : 1) * N_b * sizeof(int32_t));
+    int32_t *cnt = (int32_t *)malloc((size_t)H_q * (size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int32_t));
+    if (!I || !cnt) { free(I); free(cnt); return 1; }
+    int err;
+    if (B_r > 0) {
+        int64_t *blocks = (int64_t *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int64_t));
+        if (!blocks) { free(I); free(cnt); return 1; }
+        for (int t = 0; t < n_rows; ++t) blocks[t] = rows[t] / B_r;
+        err = dhsa_oracle_route_blocks(Q, K, H_q, H_kv, L, D, B, N_c, B_r, N_b, pooling, blocks, n_rows, I, cnt);
+        free(blocks);
+    } else {
+        err = dhsa_oracle_route_rows(Q, K, H_q, H_kv, L, D, B, N_c, N_b, pooling, rows, n_rows, I, cnt);
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < n_rows; ++t) {
+        int64_t i = rows[t];
+        const int32_t *It = I + ((int64_t)head * n_rows + t) * N_b;
+        int c = cnt[(int64_t)head * n_rows + t];
+        /* the block's list may hold keys above the row: they are masked in attention, so not retained */
+        int32_t *vis = (int32_t *)malloc((size_t)(c > 0 ? c : 1) * sizeof(int32_t));
+        int cv = 0;
+        if (!vis) { err = 1; continue; }
+        for (int v = 0; v < c; ++v)
+            if (It[v] <= i) vis[cv++] = It[v];
+        if (dhsa_oracle_recall_row(Q + ((int64_t)head * L + i) * D, K + (int64_t)(head / G) * L * D, i, D, vis, cv,
+                                   N_b, hits + t, size + t))
+            err = 1;
+        free(vis);
+    }
+    free(I); free(cnt);
+    return err;
 }

@@ -684,3 +684,63 @@ def test_mean_pooling_selects_like_eq4_on_equal_chunks_and_differently_on_unequa
     for i in (0, 17, 95):
         np.testing.assert_allclose(O1[1, i], oracle.attend_row(Q[1, i], K[0], V[0], I1[1, i, :c1[1, i]], i, 1 / math.sqrt(D)),
                                    rtol=1e-13, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# Recall against exact top-k attention (App. "Theoretical Analysis", Setup and Notation)
+# ----------------------------------------------------------------------------
+def test_recall_row_hand_example_and_brute_force():
+    # one row, logits 3, 1, 3, 2, 0 for keys 0..4 (q = [1], keys are the logits); top-2 = {0, 2} (tie of 3s)
+    q = np.array([1.0], dtype=np.float32)
+    Kg = np.array([[3.0], [1.0], [3.0], [2.0], [0.0]], dtype=np.float32)
+    assert oracle.recall_row(q, Kg, 4, np.array([0, 2]), 2) == (2, 2)
+    assert oracle.recall_row(q, Kg, 4, np.array([1, 4]), 2) == (0, 2)
+    assert oracle.recall_row(q, Kg, 4, np.array([2, 3, 4]), 2) == (1, 2)
+    # top-1 with equal best logits: the lower index wins
+    assert oracle.recall_row(q, Kg, 4, np.array([2]), 1) == (0, 1)
+    assert oracle.recall_row(q, Kg, 4, np.array([0]), 1) == (1, 1)
+    # the budget is clipped to the causal length: row 1 sees keys 0, 1 only
+    assert oracle.recall_row(q, Kg, 1, np.array([0, 1]), 4) == (2, 2)
+    rng = np.random.default_rng(31)
+    for _ in range(20):
+        L, D = int(rng.integers(5, 60)), 4
+        q = np.round(rng.standard_normal(D) * 2).astype(np.float32)      # integer-valued: ties occur
+        Kg = np.round(rng.standard_normal((L, D)) * 2).astype(np.float32)
+        i = int(rng.integers(0, L)); k = int(rng.integers(1, L + 3))
+        I_hat = np.sort(rng.choice(i + 1, size=int(rng.integers(1, i + 2)), replace=False)).astype(np.int32)
+        logits = Kg[:i + 1].astype(np.float64) @ q.astype(np.float64)
+        top = set(np.argsort(-logits, kind="stable")[:min(k, i + 1)].tolist())
+        assert oracle.recall_row(q, Kg, i, I_hat, k) == (len(top & set(I_hat.tolist())), min(k, i + 1))
+
+
+def test_recall_of_routed_sets_special_cases():
+    rng = np.random.default_rng(37)
+    H_q, H_kv, L, D = 2, 1, 120, 8
+    B = rand_boundaries(rng, L, 2, 12)
+    Q = rng.standard_normal((H_q, L, D)).astype(np.float32)
+    K = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    rows = np.arange(L)
+    # a budget of everything: both sets are all causal keys, recall 1
+    hits, size = oracle.recall_rows(Q, K, B, L, 0, rows)
+    np.testing.assert_array_equal(hits, rows + 1); np.testing.assert_array_equal(size, rows + 1)
+    # one-token chunks: chunk scores ARE the token logits, so the routed set is exactly top-k: recall 1
+    B1 = np.arange(L + 1, dtype=np.int32)
+    hits, size = oracle.recall_rows(Q, K, B1, 9, 1, rows)
+    np.testing.assert_array_equal(hits, size)
+    np.testing.assert_array_equal(size, np.minimum(9, rows + 1))
+    # general chunks: recall below 1 somewhere, and equal to an explicit set intersection
+    hits, size = oracle.recall_rows(Q, K, B, 10, 1, rows)
+    assert (hits < size).any() and (hits <= size).all()
+    I, cnt = oracle.route_rows(Q, K, B, 10, rows)
+    for i in (5, 60, 119):
+        logits = K[0, :i + 1].astype(np.float64) @ Q[1, i].astype(np.float64)
+        top = set(np.argsort(-logits, kind="stable")[:min(10, i + 1)].tolist())
+        assert hits[i] == len(top & set(I[1, i, :cnt[1, i]].tolist()))
+    # row-block form: keys of the block's list above the row do not count as retained
+    hb, sb = oracle.recall_rows(Q, K, B, 10, 0, rows, B_r=16)
+    Ib, cb = oracle.route_blocks(Q, K, B, 16, 10, rows // 16)
+    for i in (3, 40, 119):
+        logits = K[0, :i + 1].astype(np.float64) @ Q[0, i].astype(np.float64)
+        top = set(np.argsort(-logits, kind="stable")[:min(10, i + 1)].tolist())
+        vis = [j for j in Ib[0, i, :cb[0, i]].tolist() if j <= i]
+        assert hb[i] == len(top & set(vis)) and sb[i] == min(10, i + 1)
