@@ -215,6 +215,25 @@ dhsa_status dhsa_mfma_probe(int random_operands, int iters, void *scratch_dev, s
                             double *tflops_host, double *shader_mhz_host, void *stream);
 size_t dhsa_mfma_probe_scratch_bytes(void);
 
+/* Quality diagnostic (App. "Theoretical Analysis", Setup and Notation; the
+ * quantity behind "Overlap with Top-K Attention" in Sec. 4): per-row recall of
+ * the routed key sets of one head against exact top-k attention.  For every row
+ * i of the HOST list: I*_i = the k = min(N_b, i + 1) keys j <= i with the largest
+ * logits q_i . k_j (fp64, summed over d in ascending order; equal logits: lower
+ * index), I_hat_i = the keys the plan gives row i (row-block form: the keys of
+ * its block's list at or below the row).  hits_dev[t] = |I* n I_hat|,
+ * size_dev[t] = |I*| (device int32[n_rows]); recall = hits / size.
+ * plan_dev must come from dhsa_route on the same problem and boundaries.
+ * rows_dev_scratch: device int64[n_rows]; ws_dev: device scratch of
+ * dhsa_recall_workspace_bytes(prob, n_rows) bytes (8 L per row).  Asynchronous;
+ * cost O(L D) per row -- a diagnostic for sampled rows, not a step of the path. */
+dhsa_status dhsa_recall_rows(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
+                             const int32_t *B_host, const void *plan_dev, size_t plan_bytes, int32_t head,
+                             const int64_t *rows_host, int32_t n_rows, int64_t *rows_dev_scratch,
+                             void *ws_dev, size_t ws_bytes, int32_t *hits_dev, int32_t *size_dev,
+                             void *stream);
+size_t dhsa_recall_workspace_bytes(const dhsa_problem *prob, int32_t n_rows);
+
 const char *dhsa_status_string(dhsa_status s);
 int dhsa_version(void);
 

@@ -24,6 +24,7 @@ POS_SHIFT = 28
 EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse_prefill", "dhsa_prefill",
            "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
            "dhsa_finalize_boundaries", "dhsa_finalize_boundaries_workspace_bytes",
+           "dhsa_recall_rows", "dhsa_recall_workspace_bytes",
            "dhsa_status_string", "dhsa_version"]
 
 
@@ -74,6 +75,10 @@ def lib() -> C.CDLL:
         l.dhsa_finalize_boundaries.restype = C.c_int
         l.dhsa_finalize_boundaries_workspace_bytes.argtypes = [C.c_int64]
         l.dhsa_finalize_boundaries_workspace_bytes.restype = C.c_size_t
+        l.dhsa_recall_rows.argtypes = [P, vp, vp, i32p, vp, C.c_size_t, C.c_int32, i64p, C.c_int32, vp, vp, C.c_size_t,
+                                       vp, vp, vp]
+        l.dhsa_recall_rows.restype = C.c_int
+        l.dhsa_recall_workspace_bytes.argtypes = [P, C.c_int32]; l.dhsa_recall_workspace_bytes.restype = C.c_size_t
         l.dhsa_status_string.argtypes = [C.c_int]; l.dhsa_status_string.restype = C.c_char_p
         l.dhsa_version.argtypes = []; l.dhsa_version.restype = C.c_int
         _lib = l
@@ -216,6 +221,24 @@ def dhsa_finalize_boundaries(scores, threshold: float, window: int) -> np.ndarra
                                           N_c.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     torch.cuda.synchronize()
     return B[:int(N_c.item()) + 1].cpu().numpy()
+
+
+def dhsa_recall_rows(prob, Q, K, B, plan, head: int, rows) -> Tuple["torch.Tensor", "torch.Tensor"]:
+    """Recall counts of the routed sets of `rows` (host int64) of one head against exact top-k
+    attention: (hits [n], size [n]) int32 device tensors; recall = hits / size."""
+    import torch
+    B = _b(B)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    n = rows.shape[0]
+    nb = int(lib().dhsa_recall_workspace_bytes(C.byref(prob), n))
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device=plan.device)
+    scratch = torch.empty(max(n, 1), dtype=torch.int64, device=plan.device)
+    hits = torch.empty(n, dtype=torch.int32, device=plan.device)
+    size = torch.empty(n, dtype=torch.int32, device=plan.device)
+    _check(lib().dhsa_recall_rows(C.byref(prob), Q.data_ptr(), K.data_ptr(), _bp(B), plan.data_ptr(), plan.numel(),
+                                  head, rows.ctypes.data_as(C.POINTER(C.c_int64)), n, scratch.data_ptr(),
+                                  ws.data_ptr(), ws.numel(), hits.data_ptr(), size.data_ptr(), _stream()))
+    return hits, size
 
 
 def dhsa_version() -> int:

@@ -255,6 +255,37 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
                                     cnt_dev, s));
 }
 
+__attribute__((visibility("default"))) size_t dhsa_recall_workspace_bytes(const dhsa_problem *prob,
+                                                                        int32_t n_rows) {
+    if (!prob || prob->L < 1 || prob->L >= (int64_t)1 << 31 || n_rows < 0) return 0;
+    return (size_t)std::max<int64_t>((int64_t)n_rows * prob->L * 8, 256);
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_recall_rows(
+    const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const int32_t *B_host, const void *plan_dev,
+    size_t plan_bytes, int32_t head, const int64_t *rows_host, int32_t n_rows, int64_t *rows_dev_scratch,
+    void *ws_dev, size_t ws_bytes, int32_t *hits_dev, int32_t *size_dev, void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !plan_dev || !rows_host || !rows_dev_scratch || !ws_dev || !hits_dev || !size_dev)
+        return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(plan_dev) || misaligned(ws_dev)) return DHSA_ERR_ALIGN;
+    if (head < 0 || head >= p.H_q || n_rows < 0) return DHSA_ERR_SHAPE;
+    for (int t = 0; t < n_rows; ++t)
+        if (rows_host[t] < 0 || rows_host[t] >= p.L) return DHSA_ERR_SHAPE;
+    const PlanLayout pl = plan_layout(p, B_host);
+    if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
+    if (ws_bytes < dhsa_recall_workspace_bytes(prob, n_rows)) return DHSA_ERR_WORKSPACE;
+    if (n_rows == 0) return DHSA_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(rows_dev_scratch, rows_host, sizeof(int64_t) * (size_t)n_rows, hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+        return DHSA_ERR_HIP;
+    return hip_status(launch_recall(p, plan_view(pl, plan_dev), Q_dev, K_dev, head, rows_dev_scratch, n_rows,
+                                    static_cast<unsigned long long *>(ws_dev), hits_dev, size_dev, s));
+}
+
 __attribute__((visibility("default"))) dhsa_status dhsa_debug_routing(const dhsa_problem *prob,
                                                                       const int32_t *B_host, const void *ws_dev,
                                                                       size_t ws_bytes, double *Qc_dev,

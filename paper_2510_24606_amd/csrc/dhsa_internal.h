@@ -57,6 +57,9 @@ hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, cons
 hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s);
 hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
                          int32_t *idx, int cap, int32_t *cnt, hipStream_t s);
+hipError_t launch_recall(const Prob &p, const PlanView &pv, const void *Q, const void *K, int head,
+                         const int64_t *rows_dev, int n_rows, unsigned long long *ws, int32_t *hits, int32_t *size,
+                         hipStream_t s);
 hipError_t launch_attn_rowwise(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                                void *O, hipStream_t s);
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,

@@ -132,6 +132,32 @@ def test_finalize_boundaries_rejects_bad_arguments_on_the_host(lib):
     assert f(fake, 1000, 0.5, 8, fake, fake, fake, need - 1, None) == 6
 
 
+def test_recall_rows_rejects_bad_arguments_on_the_host(lib):
+    import ctypes as C
+    B = bounds()
+    p = mk()
+    fake = C.c_void_p(256)   # never dereferenced: every call below fails validation first
+    rows = (C.c_int64 * 2)(3, 999)
+    bad_rows = (C.c_int64 * 2)(3, 1000)
+    Bp = B.ctypes.data_as(C.POINTER(C.c_int32))
+    pb = dhsa.dhsa_plan_bytes(p, B)
+    need = lib.dhsa_recall_workspace_bytes(C.byref(p), 2)
+    assert need >= 2 * 1000 * 8
+    f = lib.dhsa_recall_rows
+    ok_args = [C.byref(p), fake, fake, Bp, fake, pb, 0, rows, 2, fake, fake, need, fake, fake, None]
+    def call(**kw):
+        a = list(ok_args)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    assert call(a1=None) == 1                    # Q
+    assert call(a13=None) == 1                   # size_dev
+    assert call(a6=4) == 2                       # head out of range
+    assert call(a7=bad_rows) == 2                # a row beyond L
+    assert call(a5=pb - 4) == 8                  # plan too small
+    assert call(a11=need - 8) == 6               # workspace too small
+
+
 def test_no_oracle_in_the_product_path():
     """The product package must not import, load or call the oracle."""
     pkg = os.path.join(ROOT, "paper_2510_24606_amd")

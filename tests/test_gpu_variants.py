@@ -71,3 +71,53 @@ def test_fixed_chunks_with_either_pooling_select_the_same_keys():
         torch.cuda.synchronize()
         outs.append(O)
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+# ----------------------------------------------------------------------------
+# Recall of the routed sets against exact top-k attention (integer counts, bit-exact)
+# ----------------------------------------------------------------------------
+RECALL_CASES = [
+    ("c1", dict(L=1500, N_b=200), 0, 0),
+    ("c2", dict(L=4000, H_q=4, H_kv=2, N_b=384), 0, 0),
+    ("c3", dict(L=4096, H_q=4, H_kv=2, N_b=512), 0, 1),                       # plain average pooling
+    ("c3", dict(L=4096, H_q=4, H_kv=2, N_b=512), 128, 0),                     # row blocks
+    ("c3", dict(L=2048, H_q=2, H_kv=2, D=64, N_b=100, lens=("fixed", 1)), 0, 0),   # one-token chunks: recall 1
+]
+
+
+@pytest.mark.parametrize("name,kw,B_r,pooling", RECALL_CASES,
+                         ids=[f"{n}-Br{b}-p{p}-{i}" for i, (n, _, b, p) in enumerate(RECALL_CASES)])
+def test_recall_rows_parity(name, kw, B_r, pooling):
+    w = dhsa_inputs.make(name, **kw)
+    Q, K = w.Q.cuda(), w.K.cuda()
+    prob = dhsa.problem(Q, K, w.B, w.N_b, B_r=B_r, pooling=pooling)
+    plan, ws = dhsa.alloc(prob, w.B)
+    dhsa.dhsa_route(prob, Q, K, w.B, plan, ws)
+    rows = np.arange(0, w.L, 3, dtype=np.int64)
+    for head in (0, w.H_q - 1):
+        hits, size = dhsa.dhsa_recall_rows(prob, Q, K, w.B, plan, head, rows)
+        torch.cuda.synchronize()
+        h_ref, s_ref = oracle.recall_rows(w.f32("Q"), w.f32("K"), w.B, w.N_b, head, rows, B_r=B_r, pooling=pooling)
+        np.testing.assert_array_equal(size.cpu().numpy(), s_ref)
+        np.testing.assert_array_equal(hits.cpu().numpy(), h_ref)
+        rec = hits.cpu().numpy() / np.maximum(size.cpu().numpy(), 1)
+        print(f"\n[{name} B_r={B_r} pooling={pooling} head {head}] mean recall over {len(rows)} rows = {rec.mean():.4f}",
+              flush=True)
+        if kw.get("lens") == ("fixed", 1):
+            assert (hits == size).all()
+
+
+def test_recall_rows_full_size_sample():
+    w = dhsa_inputs.make("c3")
+    Q, K = w.Q.cuda(), w.K.cuda()
+    prob = dhsa.problem(Q, K, w.B, w.N_b)
+    plan, ws = dhsa.alloc(prob, w.B)
+    dhsa.dhsa_route(prob, Q, K, w.B, plan, ws)
+    rows = dhsa_inputs.sample_rows(w, 48)
+    hits, size = dhsa.dhsa_recall_rows(prob, Q, K, w.B, plan, 5, rows)
+    torch.cuda.synchronize()
+    h_ref, s_ref = oracle.recall_rows(w.f32("Q"), w.f32("K"), w.B, w.N_b, 5, rows)
+    np.testing.assert_array_equal(size.cpu().numpy(), s_ref)
+    np.testing.assert_array_equal(hits.cpu().numpy(), h_ref)
+    print(f"\n[c3 head 5] mean recall over {len(rows)} sampled rows = "
+          f"{(hits.cpu().numpy() / size.cpu().numpy()).mean():.4f}", flush=True)
