@@ -49,7 +49,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (heads shard trivially across GPUs, see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (whole kv-head groups would shard across GPUs without any exchange); "
               "--gpus must be 1", file=sys.stderr)
         return 2
 

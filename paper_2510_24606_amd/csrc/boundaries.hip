@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kNmsThreads) void k_finalize_boundaries(const float
     const int64_t NB = (L + 63) >> 6, NW = (NB + 31) >> 5;   // 64-position blocks, bitmap words
     unsigned *dirtyA = bits0, *dirtyB = bits1, *dirtyN = bits2;   // visit now / near a new chunk end / visit next
 
-    // candidates: score strictly above the threshold (a NaN never is); every block is visited in round 1
+    // candidates: score strictly above the threshold (a NaN never is); every block is visited in the first pass
     int und = 0;
     for (int64_t i = tid; i < L; i += kNmsThreads) {
         const bool c = p[i] > tau;
