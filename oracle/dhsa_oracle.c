@@ -18,8 +18,7 @@
  *   recall diagnostic  App. "Theoretical Analysis", Setup and Notation: per-row recall of a
  *                      selected set against the top-k keys by attention score
  *
- * Readings taken where the paper is silent or has two forms (all listed in the
- * design notes of this repository):
+ * Readings taken where the paper is silent or has two forms:
  *   - queries are pooled over the same dynamic chunks as keys (Sec. 3.1/3.3), and
  *     the index set is built per query ROW: Alg. 1 with q_max = i + 1 for row i,
  *     scores taken from the row's chunk;
