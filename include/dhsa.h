@@ -40,12 +40,16 @@
  *     *_bytes calls, 256-byte aligned).  The library allocates nothing, keeps
  *     no state between calls, and never synchronises: work is enqueued on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and
- *     results are valid once the caller has synchronised that stream.
+ *     results are valid once the caller has synchronised that stream.  (Two
+ *     calls beside the path do wait for the stream and say so below:
+ *     dhsa_plan_expand_rows, which reads the plan header back, and
+ *     dhsa_mfma_probe, which times a kernel.)
  *   - Every entry point returns a dhsa_status; arguments are validated before
  *     the first device call and on error nothing is written or launched.
  *   - Inputs must be finite; N_b > L behaves as N_b = L.
  *   - Limits: D in {64, 128}; 1 <= N_c <= 8192; L < 2^31; for DHSA_BF16 one K or V
- *     head must span at most 4 GiB (L * row stride * 2 bytes).
+ *     head must span at most 4 GiB (L * row stride * 2 bytes); with B_r > 0 at
+ *     most 2^20 row blocks.
  *   - Routing arithmetic (pooling, S_c, ranking) is fp64 so that the chosen
  *     index sets do not depend on summation order beyond ~1e-13 score gaps.
  *     Attention: DHSA_BF16 uses bf16 MFMA with fp32 softmax and accumulators
@@ -186,7 +190,8 @@ size_t dhsa_finalize_boundaries_workspace_bytes(int64_t L);
 /* Expand the plan into explicit index sets I_{h,i} (Alg. 1's output) for one
  * head and a HOST list of rows: idx_dev[n_rows][cap] ascending, padded with -1,
  * cnt_dev[n_rows]; cap >= min(N_b, L).  With B_r > 0 a row gets the list of its
- * row block as Alg. 1 returns it (not yet masked causally).  rows are copied to rows_dev_scratch
+ * row block as Alg. 1 returns it (not yet masked causally).  The call reads the
+ * plan header back to check it against `prob`, so it waits for `stream`.  rows are copied to rows_dev_scratch
  * (device, n_rows int64) by the call. */
 dhsa_status dhsa_plan_expand_rows(const dhsa_problem *prob, const void *plan_dev, size_t plan_bytes,
                                   int32_t head, const int64_t *rows_host, int32_t n_rows,
