@@ -2,8 +2,9 @@
 // online softmax over the selected keys; App. C "Backend implementations").
 //
 // Work unit: (query head h, row tile): up to 128 consecutive rows of ONE query
-// chunk l.  All rows of the tile share the plan entries of (h, l); they differ
-// only through v = i + 1 - B[l].  The selected keys are walked in ascending
+// group l (a chunk; or a row block, see below).  All rows of the tile share the
+// plan entries of (h, l); they differ only through v = i + 1 - RB[l], the rows of
+// the group up to and including their own.  The selected keys are walked in ascending
 // position (softmax is order-free) and packed densely into tiles of 64 keys;
 // a packed key carries (row offset, lo, hi) with "row takes key <=> lo < v < hi".
 //
@@ -59,8 +60,7 @@ __device__ __forceinline__ int piece_swizzle(int r, int pieces_per_row) {
 // offset) straight into LDS: lane L of the wave writes bytes [16 L, 16 L + 16)
 // of the window at LDS byte address `lds_window` (wave-uniform, goes through
 // M0, which nothing else in this kernel uses).  Completion is tracked by vmcnt;
-// the caller waits and then passes a
-// barrier before anyone reads the window.
+// the caller waits and then passes a barrier before anyone reads the window.
 __device__ __forceinline__ void load16_to_lds(const char *base, unsigned byte_off, unsigned lds_window) {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
