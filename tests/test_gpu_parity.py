@@ -153,6 +153,27 @@ def test_route_then_sparse_prefill_equals_prefill_and_is_deterministic():
     assert torch.equal(O.view(torch.int16), g1["O"].view(torch.int16))
 
 
+def test_work_is_enqueued_on_the_callers_stream():
+    """The whole path on a side stream (default priority) gives the same bits as on the default stream,
+    and events recorded on that stream bracket it."""
+    w = dhsa_inputs.make("c3", L=8192, H_q=8, H_kv=2, N_b=512)
+    g = run_gpu(w)
+    side = torch.cuda.Stream()
+    Q, K, V = g["Q"], g["K"], g["V"]
+    O = torch.zeros_like(Q)
+    plan, ws = dhsa.alloc(g["prob"], w.B)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dhsa.dhsa_prefill(g["prob"], Q, K, V, w.B, O, plan, ws)
+        e1.record()
+    side.synchronize()
+    assert e0.elapsed_time(e1) > 0.0
+    assert plans_equal(plan, g["plan"])
+    assert torch.equal(O.view(torch.int16), g["O"].view(torch.int16))
+
+
 def test_strided_inputs_and_explicit_scale():
     w = dhsa_inputs.make("c2", L=3000, H_q=4, H_kv=2, N_b=256)
     big_q = torch.zeros((4, 3000, 256), dtype=torch.bfloat16, device="cuda")
