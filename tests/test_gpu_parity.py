@@ -98,6 +98,7 @@ SMALL = [
     ("c2", dict(L=5000, H_q=6, H_kv=3, N_b=4000, lens=("uniform", 4, 12))),   # > 256 plan entries per chunk
     ("c3", dict(L=3000, H_q=2, H_kv=1, N_b=700, lens=("fixed", 3000))),       # one chunk
     ("c3", dict(L=2048, H_q=2, H_kv=2, N_b=100, lens=("fixed", 1))),          # one-token chunks
+    ("c3", dict(L=8192, H_q=2, H_kv=1, N_b=64, lens=("fixed", 1))),           # N_c = 8192, the chunk-count limit
 ]
 
 
