@@ -227,14 +227,26 @@ __global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, c
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
+    // 64 x 32 slabs of both operands go through registers into LDS (rows past the end read as
+    // zero); the next slab is requested from memory before the current one is multiplied
+    constexpr int kPerThread = kScTile * kScKc / 256;
+    double ra[kPerThread], rb[kPerThread];
+#define DHSA_SC_FETCH(d0_)                                                                      \
+    _Pragma("unroll") for (int i = 0; i < kPerThread; ++i) {                                    \
+        const int x = tid + 256 * i, r = x / kScKc, c = x % kScKc;                              \
+        ra[i] = (l0 + r < N_q) ? A[(int64_t)(l0 + r) * D + (d0_) + c] : 0.0;                    \
+        rb[i] = (k0 + r < N_c) ? Bm[(int64_t)(k0 + r) * D + (d0_) + c] : 0.0;                   \
+    }
+    DHSA_SC_FETCH(0)
     for (int d0 = 0; d0 < D; d0 += kScKc) {
-        // stage 64 x 32 slabs of both operands (rows past N_c read as zero)
-        for (int x = tid; x < kScTile * kScKc; x += 256) {
-            int r = x / kScKc, c = x % kScKc;
-            sA[r][c] = (l0 + r < N_q) ? A[(int64_t)(l0 + r) * D + d0 + c] : 0.0;
-            sB[r][c] = (k0 + r < N_c) ? Bm[(int64_t)(k0 + r) * D + d0 + c] : 0.0;
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int x = tid + 256 * i, r = x / kScKc, c = x % kScKc;
+            sA[r][c] = ra[i];
+            sB[r][c] = rb[i];
         }
         __syncthreads();
+        if (d0 + kScKc < D) DHSA_SC_FETCH(d0 + kScKc)
 #pragma unroll
         for (int kk = 0; kk < kScKc; kk += 4) {
             double a[2], b[2];
@@ -251,6 +263,7 @@ __global__ __launch_bounds__(256) void k_scores(const double *__restrict__ Qc, c
         }
         __syncthreads();
     }
+#undef DHSA_SC_FETCH
     // D[i][j]: accumulator element v of a lane is row 4*v + lane/16, column lane % 16
 #pragma unroll
     for (int m = 0; m < 2; ++m)
