@@ -5,6 +5,7 @@
 // All routing arithmetic is fp64: pooled sums of bf16 inputs are then exact
 // (order-free), and S_c carries ~1e-14 absolute error, so the ranking does not
 // hinge on summation order.
+#include <algorithm>
 #include "dhsa_internal.h"
 
 namespace dhsa {
@@ -307,7 +308,8 @@ constexpr int kMaxCand = 512;     // candidates kept by the radix select
 constexpr int kSelectMin = 512;   // rows with more chunks than this use it (if the LDS allocation has room)
 
 __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
-                                                PlanLayout pl, int N_c, int N_b, int B_r, int smem_bytes) {
+                                                PlanLayout pl, int N_c, int N_b, int B_r, int smem_bytes,
+                                                int guess) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_wave[4];
     __shared__ int s_p;
@@ -353,113 +355,144 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     }
     __syncthreads();
 
-    // what gets sorted: by default the whole row, in place
+    // What gets sorted: the whole row in place, or the candidates of a radix select.  The select
+    // is tried first with `guess` chunks (the number that holds the budget if the best chunks
+    // have about the mean length): the sorted candidates are exactly the head of the full
+    // ranking, so if their lengths add up to the budget no later chunk can be listed and the
+    // short sort is the answer.  Otherwise the select is redone with `stride` chunks, the bound
+    // that always suffices.
+    const bool can_select = n > kSelectMin && pl.stride <= kMaxCand - 64 && P * 8 + kMaxCand * 12 <= smem_bytes;
+    int cap0 = 64;
+    while (cap0 < guess + (guess >> 2)) cap0 <<= 1;
     unsigned long long *skey = key;
     int *sid = id;
     int Ps = P, ns = n;
-
-    if (n > kSelectMin && pl.stride <= kMaxCand - 64 && P * 8 + kMaxCand * 12 <= smem_bytes) {
-        // ---- radix select: smallest set {key >= threshold prefix} holding the best `stride` ----
-        const int need = pl.stride < n ? pl.stride : n;
-        unsigned long long prefix = 0ull;
-        int above = 0, equal = n, shift = 64;
-        for (int pass = 0; pass < 8 && above + equal > kMaxCand; ++pass) {
-            shift = 56 - 8 * pass;
-            s_hist[tid] = 0;
-            __syncthreads();
-            for (int x = tid; x < n; x += 256) {
-                const unsigned long long k = key[x];
-                if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&s_hist[(int)((k >> shift) & 255ull)], 1);
-            }
-            __syncthreads();
-            // suffix counts over digits: thread t looks at digit 255 - t
-            const int d = 255 - tid, cnt = s_hist[d];
-            int total;
-            const int gt = block_excl_scan(cnt, s_wave, &total);   // elements of the region with a larger digit
-            const int want = need - above;                         // still to be found inside the region
-            if (gt < want && gt + cnt >= want) { s_digit = d; s_above = gt; s_equal = cnt; }
-            __syncthreads();
-            above += s_above;
-            equal = s_equal;
-            prefix = (prefix << 8) | (unsigned long long)s_digit;
-            __syncthreads();
-        }
-        if (above + equal <= kMaxCand) {
-            // ---- compact the candidates, in chunk-id order, into their own arrays ----
-            unsigned long long *ckey = reinterpret_cast<unsigned long long *>(smem + (size_t)P * 8);  // over id[]
-            int *cid = reinterpret_cast<int *>(ckey + kMaxCand);
-            const int per = (n + 255) / 256;
-            int local = 0;
-            for (int e = 0; e < per; ++e) {
-                const int x = tid * per + e;
-                if (x < n && (key[x] >> shift) >= prefix) ++local;
-            }
-            int total;
-            int slot = block_excl_scan(local, s_wave, &total);
-            __syncthreads();               // id[] is dead (ids are positions), its space is reused now
-            for (int e = 0; e < per; ++e) {
-                const int x = tid * per + e;
-                if (x < n && (key[x] >> shift) >= prefix) { ckey[slot] = key[x]; cid[slot] = x; ++slot; }
-            }
-            ns = total;
-            Ps = 64;
-            while (Ps < ns) Ps <<= 1;
-            for (int x = ns + tid; x < Ps; x += 256) { ckey[x] = 0ull; cid[x] = 0x7fffffff; }
-            skey = ckey;
-            sid = cid;
-            __syncthreads();
-        }
-    }
-
-    // ---- bitonic network; "a goes first" iff key larger, or equal and id smaller ----
-    for (int size = 2; size <= Ps; size <<= 1) {
-        for (int j = size >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (Ps >> 1); t += 256) {
-                int lo = ((t / j) * (j << 1)) + (t % j);
-                int hi = lo + j;
-                bool up = (lo & size) == 0;
-                unsigned long long ka = skey[lo], kb = skey[hi];
-                int ia = sid[lo], ib = sid[hi];
-                bool a_first = (ka > kb) || (ka == kb && ia < ib);
-                if (a_first != up) {
-                    skey[lo] = kb; skey[hi] = ka;
-                    sid[lo] = ib; sid[hi] = ia;
+    int p = 0x7fffffff, run = 0;
+    int lens[32];
+    bool id_intact = true;
+    for (int attempt = (can_select && guess < pl.stride && cap0 < kMaxCand) ? 0 : 1;; ++attempt) {
+        skey = key;
+        sid = id;
+        Ps = P;
+        ns = n;
+        if (can_select) {
+            // ---- radix select: smallest set {key >= threshold prefix} holding the best `need` ----
+            const int cap = attempt == 0 ? cap0 : kMaxCand;
+            const int goal = attempt == 0 ? guess : pl.stride;
+            const int need = goal < n ? goal : n;
+            unsigned long long prefix = 0ull;
+            int above = 0, equal = n, shift = 64;
+            for (int pass = 0; pass < 8 && above + equal > cap; ++pass) {
+                shift = 56 - 8 * pass;
+                s_hist[tid] = 0;
+                __syncthreads();
+                for (int x = tid; x < n; x += 256) {
+                    const unsigned long long k = key[x];
+                    if (pass == 0 || (k >> (shift + 8)) == prefix)
+                        atomicAdd(&s_hist[(int)((k >> shift) & 255ull)], 1);
                 }
+                __syncthreads();
+                // suffix counts over digits: thread t looks at digit 255 - t
+                const int d = 255 - tid, cnt = s_hist[d];
+                int total;
+                const int gt = block_excl_scan(cnt, s_wave, &total);   // elements of the region with a larger digit
+                const int want = need - above;                         // still to be found inside the region
+                if (gt < want && gt + cnt >= want) { s_digit = d; s_above = gt; s_equal = cnt; }
+                __syncthreads();
+                above += s_above;
+                equal = s_equal;
+                prefix = (prefix << 8) | (unsigned long long)s_digit;
+                __syncthreads();
             }
-            __syncthreads();
+            if (above + equal <= cap) {
+                // ---- compact the candidates, in chunk-id order, into their own arrays ----
+                unsigned long long *ckey = reinterpret_cast<unsigned long long *>(smem + (size_t)P * 8);  // over id[]
+                int *cid = reinterpret_cast<int *>(ckey + kMaxCand);
+                const int per = (n + 255) / 256;
+                int local = 0;
+                for (int e = 0; e < per; ++e) {
+                    const int x = tid * per + e;
+                    if (x < n && (key[x] >> shift) >= prefix) ++local;
+                }
+                int total;
+                int slot = block_excl_scan(local, s_wave, &total);
+                __syncthreads();               // id[] is dead (ids are positions), its space is reused now
+                id_intact = false;
+                for (int e = 0; e < per; ++e) {
+                    const int x = tid * per + e;
+                    if (x < n && (key[x] >> shift) >= prefix) { ckey[slot] = key[x]; cid[slot] = x; ++slot; }
+                }
+                ns = total;
+                Ps = 64;
+                while (Ps < ns) Ps <<= 1;
+                for (int x = ns + tid; x < Ps; x += 256) { ckey[x] = 0ull; cid[x] = 0x7fffffff; }
+                skey = ckey;
+                sid = cid;
+                __syncthreads();
+            } else if (attempt == 0) {
+                continue;                      // too many equal scores for the short sort
+            } else if (!id_intact) {           // whole-row sort after a first attempt: ids are positions
+                for (int x = tid; x < P; x += 256) id[x] = x < n ? x : 0x7fffffff;
+                __syncthreads();
+            }
         }
-    }
-    // rank of chunk l (beyond every candidate if it is not one of them)
-    if (tid == 0) s_p = 0x7fffffff;
-    __syncthreads();
-    for (int x = tid; x < ns; x += 256)
-        if (sid[x] == own) s_p = x;
-    __syncthreads();
-    const int p = s_p;
-    // the row's key array is dead now: reuse it as rem_by_id / pos_by_id
-    int *rem_by_id = reinterpret_cast<int *>(smem);        // [P]
-    int *pos_by_id = rem_by_id + P;                        // [P]
-    if (skey != key) {                                     // chunks that are no candidates are not listed
-        for (int x = tid; x < n; x += 256) rem_by_id[x] = 0;
-    }
-    const int per = Ps / 256 > 0 ? Ps / 256 : 1;           // consecutive ranks per thread
-    {
-        int lens[32];
+
+        // ---- bitonic network; "a goes first" iff key larger, or equal and id smaller ----
+        for (int size = 2; size <= Ps; size <<= 1) {
+            for (int j = size >> 1, lj = 31 - __clz(size >> 1); j > 0; j >>= 1, --lj) {   // j = 1 << lj
+                for (int t = tid; t < (Ps >> 1); t += 256) {
+                    int lo = ((t >> lj) << (lj + 1)) + (t & (j - 1));
+                    int hi = lo + j;
+                    bool up = (lo & size) == 0;
+                    unsigned long long ka = skey[lo], kb = skey[hi];
+                    int ia = sid[lo], ib = sid[hi];
+                    bool a_first = (ka > kb) || (ka == kb && ia < ib);
+                    if (a_first != up) {
+                        skey[lo] = kb; skey[hi] = ka;
+                        sid[lo] = ib; sid[hi] = ia;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // rank of chunk l (beyond every candidate if it is not one of them)
+        if (tid == 0) s_p = 0x7fffffff;
+        __syncthreads();
+        for (int x = tid; x < ns; x += 256)
+            if (sid[x] == own) s_p = x;
+        __syncthreads();
+        p = s_p;
+        // chunk lengths along the ranking (chunk l left out) and their exclusive prefix sum
+        const int per = Ps / 256 > 0 ? Ps / 256 : 1;           // consecutive ranks per thread
         int local = 0;
         for (int e = 0; e < per; ++e) {
             int r = tid * per + e;
             int len = 0;
             if (r < ns) {
                 int k = sid[r];
-                const int e = B[k + 1] < q_max ? B[k + 1] : q_max;
-                len = (k == own) ? 0 : e - B[k];
+                const int end = B[k + 1] < q_max ? B[k + 1] : q_max;
+                len = (k == own) ? 0 : end - B[k];
             }
             lens[e] = len;
             local += len;
         }
         int total;
-        int run = block_excl_scan(local, s_wave, &total);
-        __syncthreads();  // every thread has read its sid[]; the zero fill above is complete
+        run = block_excl_scan(local, s_wave, &total);
+        if (attempt == 0 && ns < n && total < N_b) {
+            __syncthreads();                   // every thread is done with the candidates
+            continue;
+        }
+        break;
+    }
+    // the row's key array is dead now: reuse it as rem_by_id / pos_by_id
+    int *rem_by_id = reinterpret_cast<int *>(smem);        // [P]
+    int *pos_by_id = rem_by_id + P;                        // [P]
+    if (skey != key) {                                     // chunks that are no candidates are not listed
+        for (int x = tid; x < n; x += 256) rem_by_id[x] = 0;
+    }
+    __syncthreads();  // the zero fill is complete
+    {
+        const int per = Ps / 256 > 0 ? Ps / 256 : 1;
         for (int e = 0; e < per; ++e) {
             int r = tid * per + e;
             if (r < ns) {
@@ -509,8 +542,10 @@ hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
         if (e != hipSuccess) return e;
     }
+    // chunks that hold the budget if the best chunks have about the mean length, with a margin
+    const int guess = (int)std::min<int64_t>(((int64_t)p.N_b * p.N_c * 5 / 4 + p.L - 1) / p.L + 8, 1 << 20);
     hipLaunchKernelGGL(k_select, dim3(p.N_q, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
-                       (int)shmem);
+                       (int)shmem, guess);
     return hipGetLastError();
 }
 

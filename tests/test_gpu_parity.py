@@ -243,3 +243,54 @@ def test_mfma_probe_reports_plausible_rates():
     assert 1200.0 < tf_c < 2600.0, tf_c
     assert 800.0 < tf_r <= tf_c * 1.02, (tf_r, tf_c)
     assert 500.0 < mhz_r < 2600.0 and 500.0 < mhz_c < 2600.0, (mhz_c, mhz_r)
+
+
+def _short_best_workload(tied: bool, seed: int):
+    """Many 8-token chunks whose keys share a strong direction with every query, and few
+    128-token chunks of weak noise: the best-ranked chunks are all short, so far more chunks
+    hold the budget than the mean chunk length suggests.  With `tied`, only 180 short chunks
+    keep their keys; every other key is zero, so all other chunk scores tie at exactly 0."""
+    rng = np.random.default_rng([dhsa_inputs.BASE_SEED, 77, seed])
+    lens = np.r_[np.full(1100, 8), np.full(200, 128)]
+    rng.shuffle(lens)
+    B = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    L, D, H_q, H_kv = int(B[-1]), 64, 2, 1
+    u = np.full(D, 3.0 / np.sqrt(D), dtype=np.float32)
+    Q = (0.1 * rng.standard_normal((H_q, L, D))).astype(np.float32) + u
+    K = (0.1 * rng.standard_normal((H_kv, L, D))).astype(np.float32)
+    V = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    short = np.repeat(lens == 8, lens)
+    K[:, short] += 2.0 * u
+    if tied:
+        keep = rng.choice(np.nonzero(lens == 8)[0], size=180, replace=False)
+        live = np.repeat(np.isin(np.arange(len(lens)), keep), lens)
+        K[:, ~live] = 0.0
+    return dhsa_inputs.Workload(name="short_best", L=L, H_q=H_q, H_kv=H_kv, D=D, N_b=3000, dtype="f32", B=B,
+                                Q=torch.from_numpy(Q), K=torch.from_numpy(K), V=torch.from_numpy(V), seed=seed)
+
+
+@pytest.mark.parametrize("tied", [False, True], ids=["distinct", "tied_at_zero"])
+@pytest.mark.parametrize("B_r", [0, 128])
+def test_best_chunks_much_shorter_than_the_mean(tied, B_r):
+    """The ranking is first sorted over a short candidate list sized from the mean chunk
+    length; here that list never holds the budget (and, with ties, the longer list cannot be
+    cut either), so the plan must come out of the second, longer sort."""
+    w = _short_best_workload(tied, seed=1 + int(tied))
+    print(f"\n[short-best tied={tied} B_r={B_r}] L={w.L} N_c={w.N_c} N_b={w.N_b}", flush=True)
+    Q, K, V = (t.cuda() for t in (w.Q, w.K, w.V))
+    O = torch.full_like(Q, float("nan"))
+    prob = dhsa.problem(Q, K, w.B, w.N_b, B_r=B_r)
+    plan, ws = dhsa.alloc(prob, w.B)
+    dhsa.dhsa_prefill(prob, Q, K, V, w.B, O, plan, ws)
+    torch.cuda.synchronize()
+    g = dict(prob=prob, plan=plan, ws=ws, O=O)
+    rows = np.unique(np.r_[np.arange(0, w.L, 37), w.B[1:] - 1, w.L - 1]).astype(np.int64)
+    if B_r:
+        O_ref, I_ref, cnt_ref = oracle.prefill_rows_blocks(w.f32("Q"), w.f32("K"), w.f32("V"), w.B, B_r, w.N_b,
+                                                           rows)
+    else:
+        O_ref, I_ref, cnt_ref = oracle.prefill_rows(w.f32("Q"), w.f32("K"), w.f32("V"), w.B, w.N_b, rows)
+        check_plan_all_chunks(w, g)
+    check_mask_rows(w, g, rows, I_ref, cnt_ref)
+    err = check_outputs(w, g, rows, O_ref)
+    print(f"   mask exact on {len(rows)} rows x {w.H_q} heads; max |O - oracle| = {err:.3e}", flush=True)
