@@ -286,15 +286,72 @@ hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, cons
     return hipGetLastError();
 }
 
+// Value of lane (lane ^ J) of the wave, J a power of two below 64: lane-crossing moves of the
+// vector unit where there is one (quads, rows of 16), the LDS crossbar otherwise.
+template <int J>
+__device__ __forceinline__ int lane_xor(int v) {
+    if constexpr (J == 1) return __builtin_amdgcn_mov_dpp(v, 0xB1, 0xf, 0xf, true);        // quad_perm [1,0,3,2]
+    else if constexpr (J == 2) return __builtin_amdgcn_mov_dpp(v, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+    else if constexpr (J == 4) return __builtin_amdgcn_ds_swizzle(v, 0x101F);              // xor 4 inside 32 lanes
+    else if constexpr (J == 8) return __builtin_amdgcn_mov_dpp(v, 0x128, 0xf, 0xf, true);  // row_ror 8 == xor 8
+    else if constexpr (J == 16) return __builtin_amdgcn_ds_swizzle(v, 0x401F);             // xor 16 inside 32 lanes
+    else return __shfl_xor(v, 32);
+}
+
+// Bitonic sort of PS <= 256 (key, id) pairs, one per thread of the first PS threads, "first"
+// = larger key, or equal key and smaller id.  In: skey[0..PS), sid[0..PS); out: the same
+// arrays, sorted.  Exchanges at distances below 64 stay inside a wave, the few at 64 and 128
+// go through the arrays.  Called by all 256 threads (barriers).
+template <int PS, int SIZE, int J>
+__device__ __forceinline__ void sort_step(unsigned long long &k, int &ci, unsigned long long *skey, int *sid,
+                                          int tid, bool active) {
+    unsigned long long pk = 0ull;
+    int pi = 0;
+    if constexpr (J < 64) {
+        if (active) {
+            const int lo = lane_xor<J>((int)(unsigned)k), hi = lane_xor<J>((int)(unsigned)(k >> 32));
+            pk = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+            pi = lane_xor<J>(ci);
+        }
+    } else {
+        __syncthreads();           // the previous exchange has been read
+        if (active) { skey[tid] = k; sid[tid] = ci; }
+        __syncthreads();
+        if (active) { pk = skey[tid ^ J]; pi = sid[tid ^ J]; }
+    }
+    if (active) {
+        const bool first = (k > pk) || (k == pk && ci < pi);
+        const bool want_first = ((tid & J) == 0) == ((tid & SIZE) == 0);
+        if (first != want_first) { k = pk; ci = pi; }
+    }
+    if constexpr (J > 1) sort_step<PS, SIZE, J / 2>(k, ci, skey, sid, tid, active);
+    else if constexpr (SIZE < PS) sort_step<PS, SIZE * 2, SIZE>(k, ci, skey, sid, tid, active);
+}
+
+template <int PS>
+__device__ __forceinline__ void sort_in_registers(unsigned long long *skey, int *sid, int tid) {
+    const bool active = tid < PS;      // PS is a multiple of 64: whole waves; the others only keep the barriers company
+    unsigned long long k = active ? skey[tid] : 0ull;
+    int ci = active ? sid[tid] : 0x7fffffff;
+    sort_step<PS, 2, 1>(k, ci, skey, sid, tid, active);
+    __syncthreads();
+    if (active) { skey[tid] = k; sid[tid] = ci; }
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------------------
 // Ranking + per-row budget for one (head, query chunk l): Alg. 1's Argsort and
 // walk, done once for all rows of the chunk.
 //   1. scores of key chunks 0..l -> LDS as order-preserving 64-bit integers;
 //   2. only the best `stride` chunks can ever be listed (stride bounds the number
-//      of chunks whose tokens fit the budget), so for long rows a most-significant-
-//      digit radix select (8-bit digits, LDS histograms, prefix scans) first cuts
-//      the row down to <= 512 candidates; short rows skip this;
-//   3. bitonic sort of the candidates, larger score first, equal scores lower id first;
+//      of chunks whose tokens fit the budget), so for rows of more than 256 chunks a
+//      most-significant-digit radix select (8-bit digits, LDS histograms, prefix
+//      scans) first cuts the row down to a candidate list: at first a short one,
+//      sized for chunks of about the mean length (it is the answer whenever its
+//      chunks hold the budget), else one of <= 512 that holds `stride` chunks;
+//   3. bitonic sort of the candidates (of the whole row if there was no select),
+//      larger score first, equal scores lower id first; up to 256 elements are
+//      sorted in registers, one per thread, more in LDS;
 //   4. exclusive prefix sum of chunk lengths along the ranking, chunk l left out
 //      -> rem = N_b - (tokens of other chunks before this rank);
 //   5. a chunk is kept if some row takes a token of it; kept chunks are
@@ -305,7 +362,7 @@ hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, cons
 // how many tokens of the chunk the block's list holds (pos = 3).
 // ---------------------------------------------------------------------------
 constexpr int kMaxCand = 512;     // candidates kept by the radix select
-constexpr int kSelectMin = 512;   // rows with more chunks than this use it (if the LDS allocation has room)
+constexpr int kSelectMin = 256;   // rows with more chunks than this use it; shorter rows are sorted whole, in registers
 
 __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
                                                 PlanLayout pl, int N_c, int N_b, int B_r, int smem_bytes,
@@ -363,7 +420,7 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     // that always suffices.
     const bool can_select = n > kSelectMin && pl.stride <= kMaxCand - 64 && P * 8 + kMaxCand * 12 <= smem_bytes;
     int cap0 = 64;
-    while (cap0 < guess + (guess >> 2)) cap0 <<= 1;
+    while (cap0 < guess) cap0 <<= 1;
     unsigned long long *skey = key;
     int *sid = id;
     int Ps = P, ns = n;
@@ -438,6 +495,11 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
         }
 
         // ---- bitonic network; "a goes first" iff key larger, or equal and id smaller ----
+        if (Ps <= 256) {
+            if (Ps == 64) sort_in_registers<64>(skey, sid, tid);
+            else if (Ps == 128) sort_in_registers<128>(skey, sid, tid);
+            else sort_in_registers<256>(skey, sid, tid);
+        } else
         for (int size = 2; size <= Ps; size <<= 1) {
             for (int j = size >> 1, lj = 31 - __clz(size >> 1); j > 0; j >>= 1, --lj) {   // j = 1 << lj
                 for (int t = tid; t < (Ps >> 1); t += 256) {
@@ -536,14 +598,14 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
 hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s) {
     int P = 64;
     while (P < p.N_c) P <<= 1;
-    size_t shmem = (size_t)P * 12;
+    size_t shmem = (size_t)P * 8 + std::max<size_t>((size_t)P * 4, (size_t)kMaxCand * 12);   // keys + (ids | candidates)
     if (shmem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_select),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
         if (e != hipSuccess) return e;
     }
-    // chunks that hold the budget if the best chunks have about the mean length, with a margin
-    const int guess = (int)std::min<int64_t>(((int64_t)p.N_b * p.N_c * 5 / 4 + p.L - 1) / p.L + 8, 1 << 20);
+    // chunks that hold the budget if the best chunks have about the mean length, with a margin of 1/12
+    const int guess = (int)std::min<int64_t>(((int64_t)p.N_b * p.N_c * 13 / 12 + p.L - 1) / p.L + 4, 1 << 20);
     hipLaunchKernelGGL(k_select, dim3(p.N_q, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
                        (int)shmem, guess);
     return hipGetLastError();
