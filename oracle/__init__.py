@@ -341,3 +341,17 @@ def recall_rows(Q, K, B, N_b: int, head: int, rows, B_r: int = 0, pooling: int =
                                        _p(rows, C.c_int64), n, _p(hits, C.c_int32), _p(size, C.c_int32))
     assert rc == 0
     return hits, size
+
+
+def decode_row(Q, K, V, B, N_b: int, B_r: int = 0, scale: Optional[float] = None, pooling: int = 0):
+    """The newest token of a sequence of L tokens, i.e. one decoding step with the keys restricted
+    by the same mechanism (Sec. 3.4, the remark on decoding): row L - 1 of the path above, its
+    query group being the open chunk (B_r = 0) or the open row block (B_r > 0).
+    Returns (O [H_q, D] fp64, I [H_q, N_b] (-1 padded), cnt [H_q])."""
+    L = np.asarray(Q).shape[1]
+    rows = np.array([L - 1], dtype=np.int64)
+    if B_r:
+        O, I, cnt = prefill_rows_blocks(Q, K, V, B, B_r, N_b, rows, scale, pooling)
+    else:
+        O, I, cnt = prefill_rows(Q, K, V, B, N_b, rows, scale, pooling)
+    return O[:, 0], I[:, 0], cnt[:, 0]

@@ -744,3 +744,56 @@ def test_recall_of_routed_sets_special_cases():
         top = set(np.argsort(-logits, kind="stable")[:min(10, i + 1)].tolist())
         vis = [j for j in Ib[0, i, :cb[0, i]].tolist() if j <= i]
         assert hb[i] == len(top & set(vis)) and sb[i] == min(10, i + 1)
+
+
+# ----------------------------------------------------------------------------
+# One decoding step (Sec. 3.4, the remark on decoding): the newest token's row
+# ----------------------------------------------------------------------------
+def test_decode_row_special_cases():
+    rng = np.random.default_rng(41)
+    H_q, H_kv, L, D = 4, 2, 90, 8
+    B = rand_boundaries(rng, L, 2, 12)
+    Q = rng.standard_normal((H_q, L, D)).astype(np.float32)
+    K = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    V = rng.standard_normal((H_kv, L, D)).astype(np.float32)
+    scale = 1.0 / np.sqrt(D)
+
+    def dense_last(keys, h):
+        s = (K[h // 2, keys].astype(np.float64) @ Q[h, L - 1].astype(np.float64)) * scale
+        p = np.exp(s - s.max())
+        return (p / p.sum()) @ V[h // 2, keys].astype(np.float64)
+
+    # a budget of everything: the newest token attends to every token, itself included
+    for B_r in (0, 16):
+        O, I, cnt = oracle.decode_row(Q, K, V, B, L + 5, B_r=B_r)
+        assert (cnt == L).all() and (I[:, :L] == np.arange(L)).all()
+        for h in range(H_q):
+            np.testing.assert_allclose(O[h], dense_last(np.arange(L), h), rtol=1e-12, atol=1e-12)
+    # one-token chunks: the chunk scores are the token logits q_{L-1} . k_j, so the step keeps the
+    # N_b largest of them (equal logits: lower index) -- an argsort written out here
+    B1 = np.arange(L + 1, dtype=np.int32)
+    N_b = 7
+    O, I, cnt = oracle.decode_row(Q, K, V, B1, N_b)
+    for h in range(H_q):
+        logits = K[h // 2].astype(np.float64) @ Q[h, L - 1].astype(np.float64)
+        top = np.sort(np.argsort(-logits, kind="stable")[:N_b])
+        assert cnt[h] == N_b and (I[h, :N_b] == top).all()
+        np.testing.assert_allclose(O[h], dense_last(top, h), rtol=1e-12, atol=1e-12)
+    # the queries of earlier chunks play no part in the step
+    Q2 = Q.copy()
+    Q2[:, :B[-2]] = 123.0
+    O_a, I_a, _ = oracle.decode_row(Q, K, V, B, 20)
+    O_b, I_b, _ = oracle.decode_row(Q2, K, V, B, 20)
+    assert (I_a == I_b).all() and (O_a == O_b).all()
+    # ... while the other queries of the open chunk do (Eq. 4 pools the chunk's queries); looked for
+    # over a few draws, since one perturbation need not move a key across the cut-off
+    moved = False
+    for seed in range(10):
+        r2 = np.random.default_rng(seed)
+        if B[-1] - B[-2] < 2:
+            break
+        Q3 = Q.copy()
+        Q3[:, B[-2]:L - 1] = 5.0 * r2.standard_normal((H_q, L - 1 - B[-2], D)).astype(np.float32)
+        _, I_c, _ = oracle.decode_row(Q3, K, V, B, 20)
+        moved = moved or not (I_c == I_a).all()
+    assert moved or B[-1] - B[-2] < 2
