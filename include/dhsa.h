@@ -239,6 +239,42 @@ dhsa_status dhsa_recall_rows(const dhsa_problem *prob, const void *Q_dev, const 
                              void *stream);
 size_t dhsa_recall_workspace_bytes(const dhsa_problem *prob, int32_t n_rows);
 
+/* One decoding step (Sec. 3.4, the remark on decoding: the same sparse attention
+ * applied to a newly generated token by restricting the keys it attends).  The
+ * paper gives the step no algorithm of its own; the reading taken here is that
+ * the newest token is row L - 1 of the sequence and gets exactly what the prefill
+ * path gives that row: its query group -- the open chunk [B[N_c-1], L), or with
+ * B_r > 0 the open row block -- is pooled (Eq. 4; the row block as in Alg. 1),
+ * scored against all N_c key chunks, ranked and walked with the budget N_b
+ * (Alg. 1), and the row attends to the min(N_b, L) selected keys (Alg. 2).
+ *
+ * prob / B_host describe the sequence INCLUDING the newest token (L tokens,
+ * N_c chunks; how a new token extends the boundaries -- joins the open chunk or
+ * starts a chunk -- is the caller's boundary rule).  Q_dev, K_dev, V_dev are
+ * addressed with the problem's strides like in dhsa_prefill; of Q only the rows
+ * of the open query group are read (rows below it may be unset), K and V are
+ * the caches, rows [0, L).  o_stride_* are not used: the output is
+ *   O_row_dev  [H_q][D], contiguous, input dtype;
+ * optional (either may be NULL):
+ *   idx_dev    int32 [H_q][min(N_b, L)]: the selected key positions, ascending;
+ *   cnt_dev    int32 [H_q]: their number.
+ * Workspace: ws_dev of dhsa_decode_workspace_bytes(prob, N_c_cap, L_cap) bytes,
+ * 16-byte aligned, whose layout depends only on the caps (and on H_q, H_kv, D,
+ * N_b), so one allocation serves a whole generation with N_c <= N_c_cap <= 8192
+ * and L <= L_cap.  It keeps the pooled keys between calls: kc_valid says that
+ * the pooled keys of chunks [0, kc_valid) are already in ws_dev from earlier
+ * calls with the same caps, the same K rows and the same boundaries B[0..kc_valid];
+ * they are not read again.  0 <= kc_valid <= N_c - 1 (the open chunk is always
+ * pooled anew); pass 0 on the first call.  Asynchronous on `stream`; calls that
+ * share a workspace must be ordered.  Errors as for dhsa_prefill; caps below
+ * the problem's sizes or kc_valid out of range: DHSA_ERR_SHAPE. */
+dhsa_status dhsa_decode_step(const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev,
+                             const int32_t *B_host, int32_t N_c_cap, int64_t L_cap, int32_t kc_valid,
+                             void *O_row_dev, int32_t *idx_dev, int32_t *cnt_dev, void *ws_dev, size_t ws_bytes,
+                             void *stream);
+/* 0 if the problem's scalar fields or the caps are out of range. */
+size_t dhsa_decode_workspace_bytes(const dhsa_problem *prob, int32_t N_c_cap, int64_t L_cap);
+
 const char *dhsa_status_string(dhsa_status s);
 int dhsa_version(void);
 

@@ -25,6 +25,7 @@ EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse
            "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
            "dhsa_finalize_boundaries", "dhsa_finalize_boundaries_workspace_bytes",
            "dhsa_recall_rows", "dhsa_recall_workspace_bytes",
+           "dhsa_decode_step", "dhsa_decode_workspace_bytes",
            "dhsa_status_string", "dhsa_version"]
 
 
@@ -79,6 +80,11 @@ def lib() -> C.CDLL:
                                        vp, vp, vp]
         l.dhsa_recall_rows.restype = C.c_int
         l.dhsa_recall_workspace_bytes.argtypes = [P, C.c_int32]; l.dhsa_recall_workspace_bytes.restype = C.c_size_t
+        l.dhsa_decode_step.argtypes = [P, vp, vp, vp, i32p, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp,
+                                       C.c_size_t, vp]
+        l.dhsa_decode_step.restype = C.c_int
+        l.dhsa_decode_workspace_bytes.argtypes = [P, C.c_int32, C.c_int64]
+        l.dhsa_decode_workspace_bytes.restype = C.c_size_t
         l.dhsa_status_string.argtypes = [C.c_int]; l.dhsa_status_string.restype = C.c_char_p
         l.dhsa_version.argtypes = []; l.dhsa_version.restype = C.c_int
         _lib = l
@@ -103,16 +109,19 @@ def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
-def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0, pooling: int = 0) -> dhsa_problem:
+def problem(Q, K, B, N_b: int, scale: float = 0.0, B_r: int = 0, pooling: int = 0, V=None) -> dhsa_problem:
     """Describe Q [H_q, L, D] and K [H_kv, L, D] (torch tensors, last dim contiguous).
-    B_r > 0 selects Alg. 1 as printed (row blocks of B_r rows, one index list per block)."""
+    B_r > 0 selects Alg. 1 as printed (row blocks of B_r rows, one index list per block).
+    V (same shape as K) is only needed when its strides differ from a contiguous [H_kv, L, D]."""
     import torch
     H_q, L, D = Q.shape
     H_kv = K.shape[0]
     dt = {torch.float32: DHSA_F32, torch.bfloat16: DHSA_BF16}.get(Q.dtype, -1)
     return dhsa_problem(L=L, H_q=H_q, H_kv=H_kv, D=D, N_c=len(B) - 1, N_b=N_b, dtype=dt, scale=scale,
                         q_stride_h=Q.stride(0), q_stride_l=Q.stride(1),
-                        k_stride_h=K.stride(0), k_stride_l=K.stride(1), B_r=B_r, pooling=pooling)
+                        k_stride_h=K.stride(0), k_stride_l=K.stride(1),
+                        v_stride_h=0 if V is None else V.stride(0), v_stride_l=0 if V is None else V.stride(1),
+                        B_r=B_r, pooling=pooling)
 
 
 def dhsa_plan_bytes(prob: dhsa_problem, B) -> int:
@@ -239,6 +248,35 @@ def dhsa_recall_rows(prob, Q, K, B, plan, head: int, rows) -> Tuple["torch.Tenso
                                   head, rows.ctypes.data_as(C.POINTER(C.c_int64)), n, scratch.data_ptr(),
                                   ws.data_ptr(), ws.numel(), hits.data_ptr(), size.data_ptr(), _stream()))
     return hits, size
+
+
+def dhsa_decode_workspace_bytes(prob: dhsa_problem, N_c_cap: int, L_cap: int) -> int:
+    return int(lib().dhsa_decode_workspace_bytes(C.byref(prob), N_c_cap, L_cap))
+
+
+def alloc_decode(prob: dhsa_problem, N_c_cap: int, L_cap: int, device="cuda"):
+    """Workspace of the decoding step (it keeps the pooled keys between steps)."""
+    import torch
+    n = dhsa_decode_workspace_bytes(prob, N_c_cap, L_cap)
+    if n == 0:
+        raise DhsaError(2, "problem or caps rejected by dhsa_decode_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def dhsa_decode_step(prob, Q, K, V, B, ws, N_c_cap: int, L_cap: int, kc_valid: int = 0, want_idx: bool = False):
+    """One decoding step for the newest token (row L - 1): O_row [H_q, D] in the input dtype; with
+    want_idx also (idx [H_q, min(N_b, L)] int32 ascending, cnt [H_q] int32)."""
+    import torch
+    B = _b(B)
+    O_row = torch.empty((prob.H_q, prob.D), dtype=Q.dtype, device=Q.device)
+    idx = cnt = None
+    if want_idx:
+        idx = torch.empty((prob.H_q, min(prob.N_b, prob.L)), dtype=torch.int32, device=Q.device)
+        cnt = torch.empty(prob.H_q, dtype=torch.int32, device=Q.device)
+    _check(lib().dhsa_decode_step(C.byref(prob), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B), N_c_cap, L_cap,
+                                  kc_valid, O_row.data_ptr(), idx.data_ptr() if want_idx else None,
+                                  cnt.data_ptr() if want_idx else None, ws.data_ptr(), ws.numel(), _stream()))
+    return (O_row, idx, cnt) if want_idx else O_row
 
 
 def dhsa_version() -> int:

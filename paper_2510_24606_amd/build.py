@@ -7,7 +7,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["dhsa_api.hip", "route.hip", "attn.hip", "attn_mfma.hip", "mfma_probe.hip", "boundaries.hip", "recall.hip"]
+SOURCES = ["dhsa_api.hip", "route.hip", "attn.hip", "attn_mfma.hip", "mfma_probe.hip", "boundaries.hip", "recall.hip",
+           "decode.hip"]
 LIB = os.path.join(HERE, "libdhsa.so")
 
 

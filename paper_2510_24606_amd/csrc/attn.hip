@@ -6,8 +6,6 @@
 
 namespace dhsa {
 
-struct bf16_t { uint16_t bits; };
-
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // ---------------------------------------------------------------------------

@@ -58,13 +58,21 @@ dhsa_status resolve(const dhsa_problem *in, const int32_t *B, Prob *p) {
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Most chunks any query group can list: the chunks taken before the budget is
+// met number at most 1 + (how many of the shortest chunks sum to < N_b), plus
+// the query chunk itself (in the row-block form the chunk cut by the block's end
+// may count with any shorter length: it is the "+ 1" that is not among the whole
+// chunks).
+int listed_bound(const Prob &p, std::vector<int32_t> &lens) {
+    std::sort(lens.begin(), lens.end());
+    int64_t acc = 0;
+    int n = 0;
+    while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
+    return std::min(p.N_c, n + 2);
+}
+
 PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     PlanLayout pl;
-    // most chunks any query chunk can list: the chunks taken before the budget
-    // is met number at most 1 + (how many of the shortest chunks sum to < N_b),
-    // plus the query chunk itself
-    // (in the row-block form the chunk cut by the block's end may count with any
-    // shorter length: it is the "+ 1" that is not among the whole chunks)
     std::vector<int32_t> lens(p.N_c);
     for (int k = 0; k < p.N_c; ++k) lens[k] = B[k + 1] - B[k];
     int64_t T1 = 0, T_big = 0;
@@ -79,11 +87,7 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
             T_big += lens[k] / kRowTile + (lens[k] % kRowTile > kRowTile / 2);
         }
     }
-    std::sort(lens.begin(), lens.end());
-    int64_t acc = 0;
-    int n = 0;
-    while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
-    pl.stride = std::min(p.N_c, n + 2);
+    pl.stride = listed_bound(p, lens);
     pl.T1 = (int)T1;
     pl.T_big = (int)T_big;
     pl.N_q = p.N_q;
@@ -103,6 +107,35 @@ WsLayout ws_layout(const Prob &p) {
     w.off_Sc = align_up(w.off_Kc + (int64_t)p.H_kv * p.N_c * p.D, 32);
     w.doubles = align_up(w.off_Sc + (int64_t)p.H_q * p.N_q * p.N_c, 32);
     return w;
+}
+
+// Workspace of the decoding step for up to N_c_cap chunks and L_cap tokens (the
+// layout does not depend on the step's own N_c and L, so the pooled keys stay put).
+DecodeLayout decode_layout(int H_q, int H_kv, int D, int64_t N_b, int N_c_cap, int64_t L_cap) {
+    DecodeLayout dl;
+    dl.off_Kc = 0;
+    dl.off_Qc = align_up((int64_t)H_kv * N_c_cap * D * 8, 256);
+    dl.off_Sc = align_up(dl.off_Qc + (int64_t)H_q * D * 8, 256);
+    dl.off_plan = align_up(dl.off_Sc + (int64_t)H_q * N_c_cap * 8, 256);
+    PlanLayout &pl = dl.pl;
+    pl.stride = 0;   // set per step
+    pl.T1 = pl.T_big = 0;
+    pl.N_q = 1;
+    pl.off_B = 0;
+    pl.off_RB = align_up((int64_t)N_c_cap + 1, 4);
+    pl.off_count = pl.off_RB + 4;
+    pl.off_entries = align_up(pl.off_count + H_q, 4);
+    pl.off_tiles = pl.words = pl.off_entries + (int64_t)H_q * N_c_cap * 2;
+    dl.off_part = align_up(dl.off_plan + pl.words * 4, 256);
+    dl.S_cap = (int)((std::min<int64_t>(N_b, L_cap) + kDecSlice - 1) / kDecSlice);
+    dl.bytes = align_up(dl.off_part + (int64_t)H_q * dl.S_cap * (D + 2) * 4, 256);
+    return dl;
+}
+
+bool decode_caps_ok(const dhsa_problem *prob, int32_t N_c_cap, int64_t L_cap) {
+    return prob && (prob->dtype == DHSA_F32 || prob->dtype == DHSA_BF16) && prob->H_q >= 1 && prob->H_kv >= 1 &&
+           prob->H_q % prob->H_kv == 0 && prob->H_q <= 65535 - prob->H_kv && (prob->D == 64 || prob->D == 128) &&
+           prob->N_b >= 1 && N_c_cap >= 1 && N_c_cap <= kMaxChunks && L_cap >= 1 && L_cap < (int64_t)1 << 31;
 }
 
 PlanView plan_view(const PlanLayout &pl, const void *plan) {
@@ -255,6 +288,41 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
                                     cnt_dev, s));
 }
 
+__attribute__((visibility("default"))) size_t dhsa_decode_workspace_bytes(const dhsa_problem *prob,
+                                                                          int32_t N_c_cap, int64_t L_cap) {
+    if (!decode_caps_ok(prob, N_c_cap, L_cap)) return 0;
+    return (size_t)decode_layout(prob->H_q, prob->H_kv, prob->D, prob->N_b, N_c_cap, L_cap).bytes;
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_decode_step(
+    const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev, const int32_t *B_host,
+    int32_t N_c_cap, int64_t L_cap, int32_t kc_valid, void *O_row_dev, int32_t *idx_dev, int32_t *cnt_dev,
+    void *ws_dev, size_t ws_bytes, void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !V_dev || !O_row_dev || !ws_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(O_row_dev) || misaligned(ws_dev))
+        return DHSA_ERR_ALIGN;
+    if (!decode_caps_ok(prob, N_c_cap, L_cap) || p.N_c > N_c_cap || p.L > L_cap) return DHSA_ERR_SHAPE;
+    if (kc_valid < 0 || kc_valid >= p.N_c) return DHSA_ERR_SHAPE;   // the open chunk is always pooled anew
+    DecodeLayout dl = decode_layout(p.H_q, p.H_kv, p.D, prob->N_b, N_c_cap, L_cap);
+    if (ws_bytes < (size_t)dl.bytes) return DHSA_ERR_WORKSPACE;
+    std::vector<int32_t> lens(p.N_c);
+    for (int k = 0; k < p.N_c; ++k) lens[k] = B_host[k + 1] - B_host[k];
+    dl.pl.stride = listed_bound(p, lens);
+    // first row of the open query group: the last chunk, or the last row block
+    const int rb0 = p.B_r > 0 ? (int)(((p.L - 1) / p.B_r) * p.B_r) : B_host[p.N_c - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *plan = reinterpret_cast<int32_t *>(static_cast<char *>(ws_dev) + dl.off_plan);
+    if (hipMemcpyAsync(plan + dl.pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1), hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+        return DHSA_ERR_HIP;
+    if (launch_decode_route(p, dl, N_c_cap, kc_valid, rb0, Q_dev, K_dev, ws_dev, s) != hipSuccess)
+        return DHSA_ERR_HIP;
+    return hip_status(launch_decode_attend(p, dl, rb0, Q_dev, K_dev, V_dev, ws_dev, O_row_dev, idx_dev, cnt_dev, s));
+}
+
 __attribute__((visibility("default"))) size_t dhsa_recall_workspace_bytes(const dhsa_problem *prob,
                                                                         int32_t n_rows) {
     if (!prob || prob->L < 1 || prob->L >= (int64_t)1 << 31 || n_rows < 0) return 0;
@@ -328,6 +396,6 @@ __attribute__((visibility("default"))) const char *dhsa_status_string(dhsa_statu
     return "unknown status";
 }
 
-__attribute__((visibility("default"))) int dhsa_version(void) { return 110; }
+__attribute__((visibility("default"))) int dhsa_version(void) { return 120; }
 
 }  // extern "C"

@@ -48,6 +48,16 @@ struct WsLayout {
     int64_t off_Qc, off_Kc, off_Sc, doubles;
 };
 
+// Decode workspace (byte offsets).  Kc persists between steps; the rest is scratch of one step.
+// The "plan" is a one-group plan: B [N_c_cap + 1], RB [2], count [H_q], entries [H_q][stride][2]
+// (room for stride = N_c_cap), laid out by `pl` in words from off_plan.
+struct DecodeLayout {
+    int64_t off_Kc, off_Qc, off_Sc, off_plan, off_part, bytes;
+    PlanLayout pl;
+    int S_cap;   // most key slices (workgroups per head) of the attention step
+};
+constexpr int kDecSlice = 128;   // selected keys per workgroup of the decode attention step
+
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
 hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, const int32_t *RB_dev,
@@ -55,6 +65,16 @@ hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_
 hipError_t launch_scores(const Prob &p, const double *Qc, const double *Kc, const int32_t *B_dev,
                          const int32_t *RB_dev, double *Sc, hipStream_t s);
 hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s);
+// query groups [l_first, l_first + n_groups) only; `pl`, `Sc` and `plan` are indexed by group - l_first
+hipError_t launch_select_groups(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, int l_first,
+                                int n_groups, hipStream_t s);
+// one decoding step: the kernels of decode.hip (pooling of the new chunks and the open query group,
+// scores of that group, and after the ranking the attention of the newest row)
+// rb0 = first row of the open query group; the boundaries are already in the step's plan
+hipError_t launch_decode_route(const Prob &p, const DecodeLayout &dl, int N_c_cap, int kc_valid, int rb0,
+                               const void *Q, const void *K, void *ws, hipStream_t s);
+hipError_t launch_decode_attend(const Prob &p, const DecodeLayout &dl, int rb0, const void *Q, const void *K,
+                                const void *V, void *ws, void *O_row, int32_t *idx, int32_t *cnt, hipStream_t s);
 hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
                          int32_t *idx, int cap, int32_t *cnt, hipStream_t s);
 hipError_t launch_recall(const Prob &p, const PlanView &pv, const void *Q, const void *K, int head,
@@ -66,6 +86,32 @@ hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, co
                             void *O, hipStream_t s);
 
 // ---- small device helpers ----
+// bf16 storage type (a bare 16-bit pattern; the kernels convert by hand)
+struct bf16_t { uint16_t bits; };
+
+// 16 bytes of a row as fp64 addends (the pooling kernels accumulate in fp64)
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPer16 = 4;
+    __device__ static void unpack(const uint4 &u, double *acc) {
+        acc[0] += (double)__uint_as_float(u.x);
+        acc[1] += (double)__uint_as_float(u.y);
+        acc[2] += (double)__uint_as_float(u.z);
+        acc[3] += (double)__uint_as_float(u.w);
+    }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int kPer16 = 8;
+    __device__ static void unpack(const uint4 &u, double *acc) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += (double)__uint_as_float(w[i] << 16);
+            acc[2 * i + 1] += (double)__uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
 __device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N_c, int64_t i) {
     int lo = 0, hi = N_c;  // B[lo] <= i < B[hi]
     while (hi - lo > 1) {

@@ -111,29 +111,6 @@ hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipS
 // chunks again, or with B_r > 0 the row blocks of Alg. 1, whose representation
 // is sqrt(B_r) * mean of the block's rows).
 // ---------------------------------------------------------------------------
-template <typename T> struct Elem;
-template <> struct Elem<float> {
-    static constexpr int kPer16 = 4;
-    __device__ static void unpack(const uint4 &u, double *acc) {
-        acc[0] += (double)__uint_as_float(u.x);
-        acc[1] += (double)__uint_as_float(u.y);
-        acc[2] += (double)__uint_as_float(u.z);
-        acc[3] += (double)__uint_as_float(u.w);
-    }
-};
-struct bf16_t { uint16_t bits; };
-template <> struct Elem<bf16_t> {
-    static constexpr int kPer16 = 8;
-    __device__ static void unpack(const uint4 &u, double *acc) {
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[2 * i] += (double)__uint_as_float(w[i] << 16);
-            acc[2 * i + 1] += (double)__uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-};
-
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_pool(const T *__restrict__ Q, const T *__restrict__ K,
                                               const int32_t *__restrict__ B, const int32_t *__restrict__ RB,
@@ -366,7 +343,7 @@ constexpr int kSelectMin = 256;   // rows with more chunks than this use it; sho
 
 __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, int32_t *__restrict__ plan,
                                                 PlanLayout pl, int N_c, int N_b, int B_r, int smem_bytes,
-                                                int guess) {
+                                                int guess, int l_first) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_wave[4];
     __shared__ int s_p;
@@ -376,8 +353,10 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
     const int32_t *B = plan + pl.off_B;
     const bool blocks = B_r > 0;
     const int q_max = blocks ? (plan + pl.off_RB)[l + 1] : 0x7fffffff;   // clip of the chunk lengths
-    const int own = blocks ? -1 : l;                                      // the query group's own chunk
-    const int n = blocks ? chunk_of_row(B, N_c, (int64_t)q_max - 1) + 1 : l + 1;   // visible chunks 0..n-1
+    // l indexes Sc, RB and the plan; the group's number in the sequence is l_first + l (a launch
+    // may cover a suffix of the groups, laid out from 0)
+    const int own = blocks ? -1 : l_first + l;                            // the query group's own chunk
+    const int n = blocks ? chunk_of_row(B, N_c, (int64_t)q_max - 1) + 1 : l_first + l + 1;   // visible chunks 0..n-1
     int P = 64;
     while (P < n) P <<= 1;
     unsigned long long *key = reinterpret_cast<unsigned long long *>(smem);  // [P]
@@ -596,6 +575,11 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
 }
 
 hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, hipStream_t s) {
+    return launch_select_groups(p, pl, Sc, plan, 0, p.N_q, s);
+}
+
+hipError_t launch_select_groups(const Prob &p, const PlanLayout &pl, const double *Sc, int32_t *plan, int l_first,
+                                int n_groups, hipStream_t s) {
     int P = 64;
     while (P < p.N_c) P <<= 1;
     size_t shmem = (size_t)P * 8 + std::max<size_t>((size_t)P * 4, (size_t)kMaxCand * 12);   // keys + (ids | candidates)
@@ -606,8 +590,8 @@ hipError_t launch_select(const Prob &p, const PlanLayout &pl, const double *Sc, 
     }
     // chunks that hold the budget if the best chunks have about the mean length, with a margin of 1/12
     const int guess = (int)std::min<int64_t>(((int64_t)p.N_b * p.N_c * 13 / 12 + p.L - 1) / p.L + 4, 1 << 20);
-    hipLaunchKernelGGL(k_select, dim3(p.N_q, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
-                       (int)shmem, guess);
+    hipLaunchKernelGGL(k_select, dim3(n_groups, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
+                       (int)shmem, guess, l_first);
     return hipGetLastError();
 }
 

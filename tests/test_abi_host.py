@@ -158,6 +158,41 @@ def test_recall_rows_rejects_bad_arguments_on_the_host(lib):
     assert call(a11=need - 8) == 6               # workspace too small
 
 
+def test_decode_step_rejects_bad_arguments_on_the_host(lib):
+    import ctypes as C
+    B = bounds()
+    p = mk()
+    fake = C.c_void_p(256)   # never dereferenced: every call below fails validation first
+    Bp = B.ctypes.data_as(C.POINTER(C.c_int32))
+    need = lib.dhsa_decode_workspace_bytes(C.byref(p), 16, 2000)
+    # pooled keys [H_kv][N_c_cap][D] fp64 + slice states [H_q][ceil(N_b / 128)][D + 2] fp32 at least
+    assert need >= 2 * 16 * 128 * 8 + 4 * 1 * 130 * 4
+    assert lib.dhsa_decode_workspace_bytes(C.byref(p), 0, 2000) == 0
+    assert lib.dhsa_decode_workspace_bytes(C.byref(p), 8193, 2000) == 0
+    assert lib.dhsa_decode_workspace_bytes(C.byref(p), 16, 0) == 0
+    assert lib.dhsa_decode_workspace_bytes(C.byref(mk(D=96)), 16, 2000) == 0
+    # a larger budget or cap never shrinks the workspace
+    assert lib.dhsa_decode_workspace_bytes(C.byref(mk(N_b=4096)), 16, 100000) > need
+    f = lib.dhsa_decode_step
+    ok_args = [C.byref(p), fake, fake, fake, Bp, 16, 2000, 0, fake, None, None, fake, need, None]
+    def call(**kw):
+        a = list(ok_args)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    assert call(a1=None) == 1                    # Q
+    assert call(a8=None) == 1                    # O_row
+    assert call(a11=None) == 1                   # workspace
+    assert call(a5=9) == 2                       # N_c_cap below N_c = 10
+    assert call(a6=999) == 2                     # L_cap below L = 1000
+    assert call(a7=10) == 2                      # kc_valid = N_c: the open chunk must be pooled
+    assert call(a7=-1) == 2
+    assert call(a12=need - 1) == 6               # workspace too small
+    assert call(a3=C.c_void_p(264)) == 9         # V not 16-byte aligned
+    bad = B.copy(); bad[3] = bad[2]
+    assert call(a4=bad.ctypes.data_as(C.POINTER(C.c_int32))) == 3
+
+
 def test_no_oracle_in_the_product_path():
     """The product package must not import, load or call the oracle."""
     pkg = os.path.join(ROOT, "paper_2510_24606_amd")
