@@ -46,6 +46,7 @@ def main() -> int:
                          "printed with row blocks of this many rows instead")
     ap.add_argument("--no-block-form", action="store_true",
                     help="skip the extra measurement of Alg. 1 as printed (row blocks of 128 rows)")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decoding-step timing")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -154,6 +155,38 @@ def main() -> int:
                                "random_operands_tflops": round(tf_r, 1), "random_operands_shader_mhz": round(mhz_r),
                                "attention_vs_random_operand_rate": round(achieved / tf_r, 4)}
 
+    if not args.no_decode:
+        # one decoding step for the newest token at the workload's full context (same tensors as caches):
+        # steady state = the pooled keys of the closed chunks are kept from the step before; cold = every
+        # chunk pooled anew.  HBM-bound: the selected K and V rows of every query head are read once.
+        prob_d = dhsa.problem(Q, K, w.B, w.N_b, B_r=args.B_r)
+        ws_d = dhsa.alloc_decode(prob_d, w.N_c, w.L)
+
+        O_row = torch.empty((w.H_q, w.D), dtype=Q.dtype, device=Q.device)
+
+        def time_decode(kc_valid, n):
+            for _ in range(3):
+                dhsa.dhsa_decode_step(prob_d, Q, K, V, w.B, ws_d, w.N_c, w.L, kc_valid, out=O_row)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                dhsa.dhsa_decode_step(prob_d, Q, K, V, w.B, ws_d, w.N_c, w.L, kc_valid, out=O_row)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+
+        cold_ms = time_decode(0, 20)
+        steady_ms = time_decode(w.N_c - 1, 100)
+        esz = 2 if w.dtype == "bf16" else 4
+        kv_bytes = 2.0 * w.H_q * min(w.N_b, w.L) * w.D * esz            # selected K and V rows, per query head
+        kc_bytes = 8.0 * w.H_kv * w.N_c * w.D                             # pooled keys (fp64), read by the scores
+        out["decode_step"] = {"ms_steady": round(steady_ms, 4), "ms_cold": round(cold_ms, 4),
+                              "algorithmic_hbm_bytes": kv_bytes + kc_bytes,
+                              "achieved_GBps": round((kv_bytes + kc_bytes) / (steady_ms * 1e-3) / 1e9, 1),
+                              "frac_of_hbm_peak": round((kv_bytes + kc_bytes) / (steady_ms * 1e-3) / 8e12, 4),
+                              "note": "newest token of the same sequence; steady = pooled keys of closed chunks reused"}
+
     if not args.no_cpu_baseline:
         import oracle
         Qf, Kf, Vf = w.f32("Q"), w.f32("K"), w.f32("V")
@@ -172,6 +205,10 @@ def main() -> int:
             n2 = int(min(w.L, max(48, n * args.cpu_seconds / max(dt, 1e-3))))
             dt, pairs, n = run(n2)
         full_ms = dt * 1e3 * w.pairs_per_head() / pairs        # rows are independent: scale by selected pairs
+        if "decode_step" in out and args.B_r == 0:
+            t = time.perf_counter()
+            oracle.decode_row(Qf, Kf, Vf, w.B, w.N_b)
+            out["decode_step"]["cpu_oracle_ms"] = round((time.perf_counter() - t) * 1e3, 1)
         out["cpu_baseline"] = {"value": round(full_ms, 1), "unit": "ms/layer", "cores": oracle.num_threads(),
                                "kind": "oracle",
                                "sample": f"{n} stratified rows x {w.H_q} heads incl. routing of their chunks, "

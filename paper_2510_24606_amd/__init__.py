@@ -263,12 +263,13 @@ def alloc_decode(prob: dhsa_problem, N_c_cap: int, L_cap: int, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def dhsa_decode_step(prob, Q, K, V, B, ws, N_c_cap: int, L_cap: int, kc_valid: int = 0, want_idx: bool = False):
-    """One decoding step for the newest token (row L - 1): O_row [H_q, D] in the input dtype; with
-    want_idx also (idx [H_q, min(N_b, L)] int32 ascending, cnt [H_q] int32)."""
+def dhsa_decode_step(prob, Q, K, V, B, ws, N_c_cap: int, L_cap: int, kc_valid: int = 0, want_idx: bool = False,
+                     out=None):
+    """One decoding step for the newest token (row L - 1): O_row [H_q, D] in the input dtype (written
+    into `out` if given); with want_idx also (idx [H_q, min(N_b, L)] int32 ascending, cnt [H_q] int32)."""
     import torch
     B = _b(B)
-    O_row = torch.empty((prob.H_q, prob.D), dtype=Q.dtype, device=Q.device)
+    O_row = out if out is not None else torch.empty((prob.H_q, prob.D), dtype=Q.dtype, device=Q.device)
     idx = cnt = None
     if want_idx:
         idx = torch.empty((prob.H_q, min(prob.N_b, prob.L)), dtype=torch.int32, device=Q.device)

@@ -9,7 +9,7 @@
 // Kernels of this file:
 //   k_pool_decode     pooled keys (Eq. 4) of the chunks not pooled by an earlier
 //                     step, pooled queries of the open group;
-//   k_scores_decode   that group's scores against every key chunk (one wave each);
+//   k_scores_decode   that group's scores against every key chunk (one wave per pooled key);
 //   (the ranking and the walk are k_select of route.hip, launched for one group)
 //   k_attn_decode     the selected keys are split into slices of 128; one workgroup
 //                     per (slice, head) streams its K and V rows once, 16 bytes per
@@ -28,7 +28,8 @@ namespace dhsa {
 // ---------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_pool_decode(const T *__restrict__ Q, const T *__restrict__ K,
-                                                     const int32_t *__restrict__ B, int32_t *__restrict__ RBw,
+                                                     int32_t *__restrict__ B, BoundaryTail tail,
+                                                     int32_t *__restrict__ RBw,
                                                      double *__restrict__ Qc, double *__restrict__ Kc, int H_kv,
                                                      int N_c, int N_c_cap, int kc_valid, int rb0, int L, int B_r,
                                                      int pooling, int64_t qs_h, int64_t qs_l, int64_t ks_h,
@@ -49,11 +50,14 @@ __global__ __launch_bounds__(256) void k_pool_decode(const T *__restrict__ Q, co
         X = Q + (int64_t)h * qs_h; s_l = qs_l; Xc = Qc + (int64_t)h * D;
         b0 = rb0; b1 = L;
         if (h == 0 && tid == 0) { RBw[0] = rb0; RBw[1] = L; }   // the one query group of the step's plan
+        // boundaries that came as arguments go into the workspace for the kernels after this one
+        if (h == 0 && tid <= tail.n && tail.n > 0) B[kc_valid + tid] = tail.b[tid];
     } else {
         const int k = kc_valid + blockIdx.x, g = blockIdx.y;
         if (k >= N_c) return;
         X = K + (int64_t)g * ks_h; s_l = ks_l; Xc = Kc + ((int64_t)g * N_c_cap + k) * D;
-        b0 = B[k]; b1 = B[k + 1];
+        if (tail.n > 0) { b0 = tail.b[blockIdx.x]; b1 = tail.b[blockIdx.x + 1]; }   // not yet in B (see below)
+        else { b0 = B[k]; b1 = B[k + 1]; }
     }
     const int rg = tid / TPR, col = (tid % TPR) * EPT;
     double acc[EPT];
@@ -79,20 +83,25 @@ __global__ __launch_bounds__(256) void k_pool_decode(const T *__restrict__ Q, co
 
 // ---------------------------------------------------------------------------
 // Scores of the open query group: Sc[h][k] = <Qc[h], Kc[h / G][k]>, k < N_c.
-// One wave per (h, k); grid (ceil(N_c / 4), H_q).
+// One wave per (kv-head g, chunk k): it reads the pooled key once and forms the
+// scores of the G query heads of the group.  grid (ceil(N_c / 4), H_kv).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_scores_decode(const double *__restrict__ Qc, const double *__restrict__ Kc,
                                                        double *__restrict__ Sc, int N_c, int N_c_cap, int D, int G) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int k = blockIdx.x * 4 + wave, h = blockIdx.y;
+    const int k = blockIdx.x * 4 + wave, g = blockIdx.y;
     if (k >= N_c) return;   // wave-uniform
-    const double *q = Qc + (int64_t)h * D;
-    const double *kc = Kc + ((int64_t)(h / G) * N_c_cap + k) * D;
-    double acc = 0.0;
-    for (int d = lane; d < D; d += 64) acc += q[d] * kc[d];
+    const double *kc = Kc + ((int64_t)g * N_c_cap + k) * D;
+    const double k0 = kc[lane], k1 = D > 64 ? kc[lane + 64] : 0.0;
+    for (int hh = 0; hh < G; ++hh) {
+        const int h = g * G + hh;
+        const double *q = Qc + (int64_t)h * D;
+        double acc = q[lane] * k0;
+        if (D > 64) acc += q[lane + 64] * k1;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0) Sc[(int64_t)h * N_c + k] = acc;
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+        if (lane == 0) Sc[(int64_t)h * N_c + k] = acc;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -238,25 +247,47 @@ __global__ __launch_bounds__(256) void k_attn_decode(const int32_t *__restrict__
     }
 }
 
-// Merge of the S slice states of one head into the output row; grid H_q, block D.
+// Merge of the S slice states of one head into the output row.  grid H_q, block 512:
+// the slices are dealt to 512 / D groups of D threads (thread = output column), whose
+// partial sums meet in LDS.
 template <typename T, int D>
-__global__ __launch_bounds__(D) void k_decode_combine(const float *__restrict__ part, int S, T *__restrict__ O_row) {
-    const int h = blockIdx.x, d = threadIdx.x;
+__global__ __launch_bounds__(512) void k_decode_combine(const float *__restrict__ part, int S, T *__restrict__ O_row) {
+    constexpr int NSG = 512 / D;
+    __shared__ float s_red[8];
+    __shared__ float s_ls[NSG];
+    __shared__ float s_acc[NSG][D];
+    const int h = blockIdx.x, tid = threadIdx.x, d = tid % D, sg = tid / D;
     const float *pp = part + (int64_t)h * S * (D + 2);
+    // reference exponent: the largest slice maximum
     float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, pp[(int64_t)s * (D + 2)]);
+    for (int s = tid; s < S; s += 512) M = fmaxf(M, pp[(int64_t)s * (D + 2)]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    if ((tid & 63) == 0) s_red[tid >> 6] = M;
+    __syncthreads();
+    M = s_red[0];
+#pragma unroll
+    for (int x = 1; x < 8; ++x) M = fmaxf(M, s_red[x]);
     float ls = 0.f, acc = 0.f;
-    for (int s = 0; s < S; ++s) {
+    for (int s = sg; s < S; s += NSG) {
         const float *ps = pp + (int64_t)s * (D + 2);
         const float w = (ps[0] == -INFINITY) ? 0.f : __expf(ps[0] - M);
         ls += ps[1] * w;
         acc += ps[2 + d] * w;
     }
-    DecIO<T>::store(O_row + (int64_t)h * D + d, ls > 0.f ? acc / ls : 0.f);
+    s_acc[sg][d] = acc;
+    if (d == 0) s_ls[sg] = ls;
+    __syncthreads();
+    if (tid < D) {
+        float L = 0.f, A = 0.f;
+#pragma unroll
+        for (int x = 0; x < NSG; ++x) { L += s_ls[x]; A += s_acc[x][tid]; }
+        DecIO<T>::store(O_row + (int64_t)h * D + tid, L > 0.f ? A / L : 0.f);
+    }
 }
 
 hipError_t launch_decode_route(const Prob &p, const DecodeLayout &dl, int N_c_cap, int kc_valid, int rb0,
-                               const void *Q, const void *K, void *ws, hipStream_t s) {
+                               const BoundaryTail &tail, const void *Q, const void *K, void *ws, hipStream_t s) {
     char *w8 = static_cast<char *>(ws);
     double *Kc = reinterpret_cast<double *>(w8 + dl.off_Kc), *Qc = reinterpret_cast<double *>(w8 + dl.off_Qc);
     double *Sc = reinterpret_cast<double *>(w8 + dl.off_Sc);
@@ -265,7 +296,7 @@ hipError_t launch_decode_route(const Prob &p, const DecodeLayout &dl, int N_c_ca
     dim3 grid(n_new > 1 ? n_new : 1, p.H_kv + p.H_q), block(256);
 #define DHSA_POOLD(T, DD)                                                                                      \
     hipLaunchKernelGGL((k_pool_decode<T, DD>), grid, block, 0, s, (const T *)Q, (const T *)K,                  \
-                       plan + dl.pl.off_B, plan + dl.pl.off_RB, Qc, Kc, p.H_kv, p.N_c, N_c_cap, kc_valid, rb0, \
+                       plan + dl.pl.off_B, tail, plan + dl.pl.off_RB, Qc, Kc, p.H_kv, p.N_c, N_c_cap, kc_valid, rb0, \
                        (int)p.L, p.B_r, p.pooling, p.qs_h, p.qs_l, p.ks_h, p.ks_l)
     if (p.dtype == DHSA_F32) {
         if (p.D == 64) DHSA_POOLD(float, 64); else DHSA_POOLD(float, 128);
@@ -275,7 +306,7 @@ hipError_t launch_decode_route(const Prob &p, const DecodeLayout &dl, int N_c_ca
 #undef DHSA_POOLD
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_scores_decode, dim3((p.N_c + 3) / 4, p.H_q), dim3(256), 0, s, Qc, Kc, Sc, p.N_c, N_c_cap,
+    hipLaunchKernelGGL(k_scores_decode, dim3((p.N_c + 3) / 4, p.H_kv), dim3(256), 0, s, Qc, Kc, Sc, p.N_c, N_c_cap,
                        p.D, p.G);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // ranking + walk of the one open group: group number N_q - 1 of the sequence, group 0 of this plan
@@ -295,7 +326,7 @@ hipError_t launch_decode_attend(const Prob &p, const DecodeLayout &dl, int rb0, 
                            plan + dl.pl.off_entries, dl.pl.stride, rb0, (int)p.L, (const T *)Q, (const T *)K,     \
                            (const T *)V, part, S, idx, p.N_b, cnt, p.G, p.scale, p.qs_h, p.qs_l, p.ks_h, p.ks_l,  \
                            p.vs_h, p.vs_l);                                                                       \
-        hipLaunchKernelGGL((k_decode_combine<T, DD>), dim3(p.H_q), dim3(DD), 0, s, part, S, (T *)O_row);          \
+        hipLaunchKernelGGL((k_decode_combine<T, DD>), dim3(p.H_q), dim3(512), 0, s, part, S, (T *)O_row);         \
     } while (0)
     if (p.dtype == DHSA_F32) {
         if (p.D == 64) DHSA_ATTD(float, 64); else DHSA_ATTD(float, 128);

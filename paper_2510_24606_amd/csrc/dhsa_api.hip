@@ -64,10 +64,24 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
 // may count with any shorter length: it is the "+ 1" that is not among the whole
 // chunks).
 int listed_bound(const Prob &p, std::vector<int32_t> &lens) {
-    std::sort(lens.begin(), lens.end());
+    const int32_t longest = *std::max_element(lens.begin(), lens.end());
     int64_t acc = 0;
     int n = 0;
-    while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
+    if (longest <= 1 << 16) {
+        // shortest first without a sort: count the chunks of every length (this runs once per
+        // decoding step, where a sort of the lengths would cost more than the rest of the host side)
+        std::vector<int32_t> hist((size_t)longest + 1, 0);
+        for (int32_t len : lens) ++hist[len];
+        for (int32_t len = 1; len <= longest && acc + len < p.N_b; ++len) {
+            const int64_t fit = std::min<int64_t>(hist[len], (p.N_b - 1 - acc) / len);   // acc + fit len < N_b
+            n += (int)fit;
+            acc += fit * len;
+            if (fit < hist[len]) break;
+        }
+    } else {
+        std::sort(lens.begin(), lens.end());
+        while (n < p.N_c && acc + lens[n] < p.N_b) acc += lens[n++];
+    }
     return std::min(p.N_c, n + 2);
 }
 
@@ -315,10 +329,19 @@ __attribute__((visibility("default"))) dhsa_status dhsa_decode_step(
     const int rb0 = p.B_r > 0 ? (int)(((p.L - 1) / p.B_r) * p.B_r) : B_host[p.N_c - 1];
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t *plan = reinterpret_cast<int32_t *>(static_cast<char *>(ws_dev) + dl.off_plan);
-    if (hipMemcpyAsync(plan + dl.pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1), hipMemcpyHostToDevice, s) !=
-        hipSuccess)
+    // The boundaries B[0 .. kc_valid] are in the workspace already (the caller vouches for it).  The
+    // others travel as kernel arguments when they are few (the usual step adds one or two), so that a
+    // steady-state step issues no copy from host memory; otherwise all of B is copied.
+    BoundaryTail tail;
+    tail.n = 0;
+    if (kc_valid > 0 && p.N_c - kc_valid <= kBoundaryTailMax) {
+        tail.n = p.N_c - kc_valid;
+        for (int j = 0; j <= tail.n; ++j) tail.b[j] = B_host[kc_valid + j];
+    } else if (hipMemcpyAsync(plan + dl.pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
+                              hipMemcpyHostToDevice, s) != hipSuccess) {
         return DHSA_ERR_HIP;
-    if (launch_decode_route(p, dl, N_c_cap, kc_valid, rb0, Q_dev, K_dev, ws_dev, s) != hipSuccess)
+    }
+    if (launch_decode_route(p, dl, N_c_cap, kc_valid, rb0, tail, Q_dev, K_dev, ws_dev, s) != hipSuccess)
         return DHSA_ERR_HIP;
     return hip_status(launch_decode_attend(p, dl, rb0, Q_dev, K_dev, V_dev, ws_dev, O_row_dev, idx_dev, cnt_dev, s));
 }

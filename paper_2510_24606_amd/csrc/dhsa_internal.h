@@ -57,6 +57,13 @@ struct DecodeLayout {
     int S_cap;   // most key slices (workgroups per head) of the attention step
 };
 constexpr int kDecSlice = 128;   // selected keys per workgroup of the decode attention step
+// Boundaries B[kc_valid .. kc_valid + n] of the chunks a decoding step pools anew, passed by
+// value when they are few (n = 0: the kernels read all boundaries from the workspace).
+constexpr int kBoundaryTailMax = 6;
+struct BoundaryTail {
+    int n;
+    int32_t b[kBoundaryTailMax + 1];
+};
 
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
@@ -72,7 +79,7 @@ hipError_t launch_select_groups(const Prob &p, const PlanLayout &pl, const doubl
 // scores of that group, and after the ranking the attention of the newest row)
 // rb0 = first row of the open query group; the boundaries are already in the step's plan
 hipError_t launch_decode_route(const Prob &p, const DecodeLayout &dl, int N_c_cap, int kc_valid, int rb0,
-                               const void *Q, const void *K, void *ws, hipStream_t s);
+                               const BoundaryTail &tail, const void *Q, const void *K, void *ws, hipStream_t s);
 hipError_t launch_decode_attend(const Prob &p, const DecodeLayout &dl, int rb0, const void *Q, const void *K,
                                 const void *V, void *ws, void *O_row, int32_t *idx, int32_t *cnt, hipStream_t s);
 hipError_t launch_expand(const Prob &p, const PlanView &pv, int head, const int64_t *rows_dev, int n_rows,
