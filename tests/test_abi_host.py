@@ -63,6 +63,36 @@ def test_sizes(lib):
     assert dhsa.dhsa_workspace_bytes(mk(B_r=10), B) >= 8 * (4 * 100 * 128 + 2 * 10 * 128 + 4 * 100 * 10)
 
 
+def test_plan_size_follows_the_documented_layout(lib):
+    """Plan words = header 16 | B | counts | entries [H_q][N_c][stride][2] | tiles, where stride =
+    min(N_c, n + 2) and n = how many of the shortest chunks have lengths summing to less than N_b
+    (recomputed here with a sort; the library counts lengths, and sorts only for very long chunks)."""
+    rng = np.random.default_rng(3)
+    al = lambda x, a: (x + a - 1) // a * a
+    for case in range(40):
+        N_c = int(rng.integers(1, 300))
+        hi = 70000 if case % 8 == 7 else int(rng.integers(1, 400))       # some chunks past the counting range
+        lens = rng.integers(1, hi + 1, size=N_c)
+        if case % 8 == 7:
+            lens[rng.integers(0, N_c)] = 70000
+        B = np.r_[0, np.cumsum(lens)].astype(np.int32)
+        L = int(B[-1])
+        N_b = int(rng.integers(1, max(2, L)))
+        H_q = 4
+        p = mk(L=L, H_q=H_q, H_kv=2, N_c=N_c, N_b=N_b)
+        srt = np.sort(lens)
+        acc, n = 0, 0
+        while n < N_c and acc + srt[n] < N_b:
+            acc += int(srt[n]); n += 1
+        stride = min(N_c, n + 2)
+        T1 = int(((lens + 127) // 128).sum())
+        off_count = al(16 + N_c + 1, 4)
+        off_entries = al(off_count + H_q * N_c, 4)
+        off_tiles = al(off_entries + H_q * N_c * stride * 2, 4)
+        words = al(off_tiles + 2 * T1, 64)
+        assert dhsa.dhsa_plan_bytes(p, B) == 4 * words, (case, N_c, N_b, stride)
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(dtype=7), 5),
     (dict(L=0), 2),
