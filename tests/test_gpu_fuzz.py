@@ -1,6 +1,7 @@
 """Seeded random small problems through the C ABI against the oracle, every row: shapes, chunk laws,
 budgets, head groupings, both dtypes, both head sizes, the row form and the row-block form, both
-chunk representations.  Integer results bit-exact, outputs within the tolerance of the dtype."""
+chunk representations; each also runs the recall diagnostic on a few rows and one decoding step for
+its newest token.  Integer results bit-exact, outputs within the tolerance of the dtype."""
 import numpy as np
 import pytest
 import torch
@@ -80,3 +81,11 @@ def test_random_small_problem(seed):
     h_ref, s_ref = oracle.recall_rows(Qf, Kf, c["B"], c["N_b"], Q.shape[0] - 1, rr, B_r=c["B_r"], pooling=c["pooling"])
     np.testing.assert_array_equal(hits.cpu().numpy(), h_ref)
     np.testing.assert_array_equal(size.cpu().numpy(), s_ref)
+    # one decoding step for the newest token: the last row of the same problem
+    wsd = dhsa.alloc_decode(prob, len(c["B"]) - 1, c["L"])
+    O_row, idx_d, cnt_d = dhsa.dhsa_decode_step(prob, Q, K, V, c["B"], wsd, len(c["B"]) - 1, c["L"], 0, want_idx=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cnt_d.cpu().numpy(), cnt_ref[:, -1])
+    np.testing.assert_array_equal(idx_d.cpu().numpy(), I_ref[:, -1, :idx_d.shape[1]])
+    err_d = np.abs(O_row.float().cpu().numpy().astype(np.float64) - O_ref[:, -1]).max()
+    assert err_d <= TOL[c["dtype"]], err_d
