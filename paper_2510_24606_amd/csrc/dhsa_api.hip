@@ -85,10 +85,23 @@ int listed_bound(const Prob &p, std::vector<int32_t> &lens) {
     return std::min(p.N_c, n + 2);
 }
 
+// How many chunks the ranking kernel puts on its first, short candidate list: enough to hold the
+// budget if the best chunks were drawn at random from the length distribution, m mu - z sigma sqrt(m)
+// >= N_b with z = 2.5 (the kernel checks the list it gets and falls back to the safe bound
+// `stride`, so this only trades a rare second pass against a longer first sort).
+int first_list_guess(const Prob &p, const std::vector<int32_t> &lens) {
+    double sum = 0.0, sq = 0.0;
+    for (int32_t len : lens) { sum += len; sq += (double)len * len; }
+    const double mu = sum / p.N_c, var = std::max(0.0, sq / p.N_c - mu * mu), zs = 2.5 * sqrt(var);
+    const double rt = (zs + sqrt(zs * zs + 4.0 * mu * p.N_b)) / (2.0 * mu);
+    return (int)std::min(rt * rt + 3.0, 1048576.0);
+}
+
 PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     PlanLayout pl;
     std::vector<int32_t> lens(p.N_c);
     for (int k = 0; k < p.N_c; ++k) lens[k] = B[k + 1] - B[k];
+    pl.guess = first_list_guess(p, lens);
     int64_t T1 = 0, T_big = 0;
     if (p.B_r > 0) {
         const int64_t full = p.L / p.B_r, tail = p.L % p.B_r;     // row blocks of B_r rows, one shorter block
@@ -132,7 +145,7 @@ DecodeLayout decode_layout(int H_q, int H_kv, int D, int64_t N_b, int N_c_cap, i
     dl.off_Sc = align_up(dl.off_Qc + (int64_t)H_q * D * 8, 256);
     dl.off_plan = align_up(dl.off_Sc + (int64_t)H_q * N_c_cap * 8, 256);
     PlanLayout &pl = dl.pl;
-    pl.stride = 0;   // set per step
+    pl.stride = pl.guess = 0;   // set per step
     pl.T1 = pl.T_big = 0;
     pl.N_q = 1;
     pl.off_B = 0;
@@ -287,7 +300,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
         hdr[14] != (prob->B_r > 0 ? (int32_t)((prob->L + prob->B_r - 1) / prob->B_r) : prob->N_c))
         return DHSA_ERR_PLAN;
     PlanLayout pl;
-    pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12]; pl.N_q = hdr[14];
+    pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12]; pl.N_q = hdr[14]; pl.guess = 0;
     pl.off_B = hdr[8]; pl.off_RB = hdr[13]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
     pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
@@ -324,6 +337,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_decode_step(
     if (ws_bytes < (size_t)dl.bytes) return DHSA_ERR_WORKSPACE;
     std::vector<int32_t> lens(p.N_c);
     for (int k = 0; k < p.N_c; ++k) lens[k] = B_host[k + 1] - B_host[k];
+    dl.pl.guess = first_list_guess(p, lens);
     dl.pl.stride = listed_bound(p, lens);
     // first row of the open query group: the last chunk, or the last row block
     const int rb0 = p.B_r > 0 ? (int)(((p.L - 1) / p.B_r) * p.B_r) : B_host[p.N_c - 1];

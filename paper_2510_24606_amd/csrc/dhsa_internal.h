@@ -30,6 +30,7 @@ struct PlanLayout {
     int T1;           // row tiles per head
     int T_big;        // ... of which have more than 64 rows (listed first)
     int N_q;          // query groups (chunks, or row blocks)
+    int guess;        // chunks the ranking kernel lists first (see first_list_guess in dhsa_api.hip)
     int64_t off_B, off_RB, off_count, off_entries, off_tiles, words;
 };
 

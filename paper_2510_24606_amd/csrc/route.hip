@@ -588,10 +588,8 @@ hipError_t launch_select_groups(const Prob &p, const PlanLayout &pl, const doubl
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
         if (e != hipSuccess) return e;
     }
-    // chunks that hold the budget if the best chunks have about the mean length, with a margin of 1/12
-    const int guess = (int)std::min<int64_t>(((int64_t)p.N_b * p.N_c * 13 / 12 + p.L - 1) / p.L + 4, 1 << 20);
     hipLaunchKernelGGL(k_select, dim3(n_groups, p.H_q), dim3(256), shmem, s, Sc, plan, pl, p.N_c, p.N_b, p.B_r,
-                       (int)shmem, guess, l_first);
+                       (int)shmem, pl.guess > 0 ? pl.guess : 1, l_first);
     return hipGetLastError();
 }
 
