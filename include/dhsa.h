@@ -17,6 +17,10 @@
  *      (Alg. 2 / Alg. 3; App. C "Backend implementations").
  * Steps 1-4 are dhsa_route (result: a compact routing plan), step 5 is
  * dhsa_sparse_prefill, dhsa_prefill runs both on one stream.
+ * Beside the path: dhsa_finalize_boundaries (boundary scores -> B, Sec. 3.2),
+ * dhsa_recall_rows (recall of the routed sets against exact top-k attention),
+ * dhsa_decode_step (the newest token's row alone, over cached K / V), and the
+ * inspection hooks dhsa_plan_expand_rows, dhsa_debug_routing, dhsa_mfma_probe.
  *
  * With B_r > 0 in the problem struct the same entry points run Alg. 1 as it is
  * printed (App. C) instead of the per-row form above: queries are grouped in
