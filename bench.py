@@ -96,21 +96,33 @@ def main() -> int:
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / args.steps
         ms = e0.elapsed_time(e1) / args.steps
-        return ms, float(np.mean([a.elapsed_time(b) for a, b in evs])), wall
+        return ms, float(np.mean([a.elapsed_time(b) for a, b in evs])), wall, plan
 
-    ms_per_step, attn_ms, wall_ms = measure(args.B_r)
+    ms_per_step, attn_ms, wall_ms, plan_main = measure(args.B_r)
     route_ms = ms_per_step - attn_ms
 
-    def listed_pairs(B_r):
-        """(row, key) pairs per head.  Row form: sum_i min(N_b, i+1).  Row-block form: rows x min(N_b, block
-        end) summed over blocks (the pairs the causal mask removes inside a block's own range are not
-        subtracted: under 1 % at these sizes)."""
+    def attended_pairs(B_r, plan):
+        """(row, key) pairs the attention step computes on, all heads.  Row form: H_q sum_i min(N_b, i+1).
+        Row-block form: counted exactly from the plan -- per block and listed chunk (first `t` tokens of
+        chunk k, from b0 = B[k]) row i attends min(max(i + 1 - b0, 0), t) of them (the causal mask inside
+        the block's own range is taken off, not just the listed size)."""
         if B_r == 0:
-            return float(w.pairs_per_head())
-        ends = np.minimum((np.arange((w.L + B_r - 1) // B_r) + 1) * B_r, w.L)
-        return float((np.diff(np.r_[0, ends]) * np.minimum(min(w.N_b, w.L), ends)).sum())
+            return float(w.pairs_per_head()) * w.H_q
+        P = dhsa.parse_plan(plan.cpu().numpy())
+        Bk, RB = P["B"].astype(np.int64), P["RB"].astype(np.int64)
+        ent, cnt = P["entries"], P["count"]
+        live = np.arange(ent.shape[2])[None, None, :] < cnt[:, :, None]
+        k = np.where(live, ent[..., 0] & ((1 << dhsa.POS_SHIFT) - 1), 0).astype(np.int64)
+        t = np.where(live, ent[..., 1], 0).astype(np.int64)
+        b0 = Bk[k]
+        r0, r1 = RB[:-1][None, :, None], RB[1:][None, :, None]
+        a = np.maximum(r0, b0)                                    # first row that sees a token of the chunk
+        n1 = np.maximum(0, np.minimum(r1 - 1, b0 + t - 1) - a + 1)    # rows that see a growing part of it
+        n2 = np.maximum(0, r1 - 1 - np.maximum(a - 1, b0 + t - 1))    # rows that see all t
+        tot = np.where(a < r1, n1 * (a + 1 - b0) + n1 * (n1 - 1) // 2 + n2 * t, 0)
+        return float(tot.sum())
 
-    flops = 4.0 * w.D * listed_pairs(args.B_r) * w.H_q      # selected (row, key) pairs only
+    flops = 4.0 * w.D * attended_pairs(args.B_r, plan_main)      # selected (row, key) pairs only
     achieved = flops / (attn_ms * 1e-3) / 1e12
     out = {
         "metric": "DHSA prefill ms/layer @128K, 6.25% density; % of MFMA bf16 peak"
@@ -137,15 +149,17 @@ def main() -> int:
         "paper_context": PAPER_CONTEXT,
     }
     if not args.no_block_form and args.B_r == 0:
-        # Alg. 1 as printed on the same tensors: row blocks of B_r = 128 rows, one list of N_b keys per block,
-        # causal mask per token
-        B_r = 128
-        ms_b, attn_b, _ = measure(B_r)
-        fl_b = 4.0 * w.D * listed_pairs(B_r) * w.H_q
-        out["alg1_block_form"] = {"B_r": B_r, "ms_per_layer": round(ms_b, 4), "sparse_attention_ms": round(attn_b, 4),
-                                  "route_ms": round(ms_b - attn_b, 4), "flop_listed_pairs": fl_b,
-                                  "achieved_tflops": round(fl_b / (attn_b * 1e-3) / 1e12, 3),
-                                  "frac_of_bf16_mfma_peak": round(fl_b / (attn_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5)}
+        # Alg. 1 as printed on the same tensors: row blocks of B_r rows, one list of N_b keys per block,
+        # causal mask per token.  B_r = 128 is the paper's tile height (App. C); with B_r = 256 two row
+        # tiles share one list and, running side by side, find each other's K / V rows in the L2.
+        for B_r, key in ((128, "alg1_block_form"), (256, "alg1_block_form_Br256")):
+            ms_b, attn_b, _, plan_b = measure(B_r)
+            fl_b = 4.0 * w.D * attended_pairs(B_r, plan_b)
+            out[key] = {"B_r": B_r, "ms_per_layer": round(ms_b, 4), "sparse_attention_ms": round(attn_b, 4),
+                        "route_ms": round(ms_b - attn_b, 4), "flop_attended_pairs": fl_b,
+                        "achieved_tflops": round(fl_b / (attn_b * 1e-3) / 1e12, 3),
+                        "frac_of_bf16_mfma_peak": round(fl_b / (attn_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5)}
+            del plan_b
     # what the matrix unit alone sustains on this chip (same instruction as the attention kernel):
     # with operands that never change, and with random operands (the chip then clocks down to stay
     # inside its power limit, as it does on real attention data)
