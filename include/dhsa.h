@@ -167,6 +167,27 @@ dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void
                          const int32_t *B_host, void *O_dev, void *plan_dev, size_t plan_bytes,
                          void *ws_dev, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: dhsa_prefill without a
+ * workspace argument.  The routing scratch (pooled vectors and S_c) lives in a
+ * static device array of DHSA_STATIC_SCRATCH_BYTES inside the library (one copy
+ * per GPU the library runs on, held until the process ends), and the boundaries
+ * reach the device as kernel arguments instead of a copy from host memory, so
+ * the call issues kernel launches only: no hipMalloc / hipFree, no copy.
+ * Everything else is dhsa_prefill: same arguments, same kernels, same results
+ * (plan_dev and O_dev are the caller's).  A problem whose
+ * dhsa_workspace_bytes() exceeds dhsa_static_scratch_bytes() is rejected with
+ * DHSA_ERR_WORKSPACE before anything is launched (64 MiB holds e.g. L = 32768
+ * with 32 query heads and ~410 chunks).  All calls on one GPU share that GPU's
+ * array: calls that may overlap on one GPU (different streams, different host
+ * threads) race on it and must be ordered by the caller; the array keeps the
+ * last call's contents and nothing in it has to start at zero. */
+#define DHSA_STATIC_SCRATCH_BYTES (64u << 20)
+dhsa_status dhsa_prefill_static(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
+                                const void *V_dev, const int32_t *B_host, void *O_dev, void *plan_dev,
+                                size_t plan_bytes, void *stream);
+size_t dhsa_static_scratch_bytes(void);
+
 /* The step just before the path: boundary scores -> chunk boundaries (Sec. 3.2
  * "Inference Pipeline"; App. "Inference of the Boundary Predictor").
  * scores_dev[i], i in [0, L), is the predictor's score that position i marks the

@@ -22,6 +22,7 @@ PLAN_MAGIC = 0x41534844
 POS_SHIFT = 28
 
 EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse_prefill", "dhsa_prefill",
+           "dhsa_prefill_static", "dhsa_static_scratch_bytes",
            "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
            "dhsa_finalize_boundaries", "dhsa_finalize_boundaries_workspace_bytes",
            "dhsa_recall_rows", "dhsa_recall_workspace_bytes",
@@ -65,6 +66,9 @@ def lib() -> C.CDLL:
         l.dhsa_sparse_prefill.restype = C.c_int
         l.dhsa_prefill.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp, C.c_size_t, vp]
         l.dhsa_prefill.restype = C.c_int
+        l.dhsa_prefill_static.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp]
+        l.dhsa_prefill_static.restype = C.c_int
+        l.dhsa_static_scratch_bytes.argtypes = []; l.dhsa_static_scratch_bytes.restype = C.c_size_t
         l.dhsa_plan_expand_rows.argtypes = [P, vp, C.c_size_t, C.c_int32, i64p, C.c_int32, vp, vp, C.c_int32, vp, vp]
         l.dhsa_plan_expand_rows.restype = C.c_int
         l.dhsa_debug_routing.argtypes = [P, i32p, vp, C.c_size_t, vp, vp, vp, vp]
@@ -169,6 +173,18 @@ def dhsa_prefill(prob, Q, K, V, B, O, plan, ws) -> None:
     p = _with_vo(prob, V, O)
     _check(lib().dhsa_prefill(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B), O.data_ptr(),
                               plan.data_ptr(), plan.numel(), ws.data_ptr(), ws.numel(), _stream()))
+
+
+def dhsa_prefill_static(prob, Q, K, V, B, O, plan) -> None:
+    """dhsa_prefill with the routing scratch in the library's static device array (no workspace)."""
+    B = _b(B)
+    p = _with_vo(prob, V, O)
+    _check(lib().dhsa_prefill_static(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B), O.data_ptr(),
+                                     plan.data_ptr(), plan.numel(), _stream()))
+
+
+def dhsa_static_scratch_bytes() -> int:
+    return int(lib().dhsa_static_scratch_bytes())
 
 
 def dhsa_plan_expand_rows(prob, plan, head: int, rows) -> Tuple["torch.Tensor", "torch.Tensor"]:

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "dhsa_internal.h"
@@ -182,12 +183,14 @@ PlanView plan_view(const PlanLayout &pl, const void *plan) {
 
 dhsa_status hip_status(hipError_t e) { return e == hipSuccess ? DHSA_OK : DHSA_ERR_HIP; }
 
+// b_by_args: the boundaries travel as kernel arguments instead of a copy from host memory
 dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, const void *Q, const void *K,
-                       const int32_t *B_host, void *plan, void *ws, hipStream_t s) {
+                       const int32_t *B_host, void *plan, void *ws, hipStream_t s, bool b_by_args = false) {
     int32_t *pw = static_cast<int32_t *>(plan);
     double *wd = static_cast<double *>(ws);
-    hipError_t e = hipMemcpyAsync(pw + pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
-                                  hipMemcpyHostToDevice, s);
+    hipError_t e = b_by_args ? launch_put_boundaries(B_host, p.N_c + 1, pw + pl.off_B, s)
+                             : hipMemcpyAsync(pw + pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
+                                              hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return DHSA_ERR_HIP;
     if ((e = launch_setup(p, pl, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
     if ((e = launch_pool(p, Q, K, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Qc, wd + wl.off_Kc, s)) != hipSuccess)
@@ -206,6 +209,29 @@ dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, cons
     hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
                                           : launch_attn_rowwise(p, pv, Q, K, V, O, s);
     return hip_status(e);
+}
+
+// ---- routing scratch of dhsa_prefill_static ----
+// One array per GPU, created when the code object is loaded there and held until the process
+// ends.  Host code never uses the array's name as an address: the device address is looked up
+// once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)DHSA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void *g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device; nullptr if it cannot be had.
+void *static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
 }
 
 }  // namespace
@@ -273,6 +299,33 @@ __attribute__((visibility("default"))) dhsa_status dhsa_prefill(const dhsa_probl
     if (plan_bytes < (size_t)pl.words * 4 || ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, s);
+    if (st != DHSA_OK) return st;
+    return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
+}
+
+__attribute__((visibility("default"))) size_t dhsa_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+__attribute__((visibility("default"))) dhsa_status dhsa_prefill_static(const dhsa_problem *prob, const void *Q_dev,
+                                                                       const void *K_dev, const void *V_dev,
+                                                                       const int32_t *B_host, void *O_dev,
+                                                                       void *plan_dev, size_t plan_bytes,
+                                                                       void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) || misaligned(O_dev))
+        return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    const WsLayout wl = ws_layout(p);
+    if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_WORKSPACE;
+    if ((size_t)wl.doubles * 8 > kStaticScratchBytes) return DHSA_ERR_WORKSPACE;   // beyond the static scratch
+    void *ws = static_scratch();
+    if (!ws) return DHSA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // nothing in the scratch has to start at zero: the pooled vectors and every score the ranking
+    // reads are written by this call before they are read
+    st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws, s, /*b_by_args=*/true);
     if (st != DHSA_OK) return st;
     return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
 }

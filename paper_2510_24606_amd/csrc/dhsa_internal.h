@@ -66,7 +66,17 @@ struct BoundaryTail {
     int32_t b[kBoundaryTailMax + 1];
 };
 
+// Up to kBoundaryBlockMax boundaries passed by value to a kernel (a launch argument block
+// holds at most 4 KiB), for callers whose boundary array must not go through a host copy.
+constexpr int kBoundaryBlockMax = 960;
+struct BoundaryBlock {
+    int32_t first, n;
+    int32_t b[kBoundaryBlockMax];
+};
+
 // ---- launchers (each enqueues on `s` and returns the launch status) ----
+// B_host[0 .. n) -> B_dev, carried by kernel arguments (no copy engine, no staging buffer)
+hipError_t launch_put_boundaries(const int32_t *B_host, int n, int32_t *B_dev, hipStream_t s);
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s);
 hipError_t launch_pool(const Prob &p, const void *Q, const void *K, const int32_t *B_dev, const int32_t *RB_dev,
                        double *Qc, double *Kc, hipStream_t s);

@@ -104,6 +104,28 @@ hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipS
 }
 
 // ---------------------------------------------------------------------------
+// Boundaries into the plan without a copy from host memory: each launch carries
+// up to kBoundaryBlockMax of them as kernel arguments.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_put_boundaries(int32_t *__restrict__ dst, BoundaryBlock blk) {
+    for (int i = threadIdx.x; i < blk.n; i += 256) dst[blk.first + i] = blk.b[i];
+}
+
+hipError_t launch_put_boundaries(const int32_t *B_host, int n, int32_t *B_dev, hipStream_t s) {
+    BoundaryBlock blk;
+    for (int first = 0; first < n; first += kBoundaryBlockMax) {
+        blk.first = first;
+        blk.n = std::min(kBoundaryBlockMax, n - first);
+        for (int i = 0; i < blk.n; ++i) blk.b[i] = B_host[first + i];
+        for (int i = blk.n; i < kBoundaryBlockMax; ++i) blk.b[i] = 0;
+        hipLaunchKernelGGL(k_put_boundaries, dim3(1), dim3(256), 0, s, B_dev, blk);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------
 // Chunk pooling, Eq. 4: X_c[h, k, :] = (sqrt(len)/len) * sum_{i in chunk k} X[h, i, :].
 // One block per (chunk, head); a row of D elements is read by D*sizeof(T)/16
 // threads with 16-byte loads, row groups are summed through LDS.  HBM-bound.
