@@ -514,6 +514,84 @@ def test_blocks_that_coincide_with_chunks_reduce_to_the_row_form():
         np.testing.assert_array_equal(Ib, Ir)
 
 
+def _swap_gap(S_row, B, q_max, N_b):
+    """Near-tie gap of one row block from its definition, by trial: the smallest |score gap| over pairs
+    of adjacently ranked visible chunks whose exchange changes the block's list (Alg. 1 walk, written out)."""
+    order = [int(k) for k in oracle.rank(S_row) if B[k] < q_max]
+
+    def takes(seq):
+        room, out = N_b, {}
+        for k in seq:
+            t = max(0, min(room, min(int(B[k + 1]), q_max) - int(B[k])))
+            out[k] = t
+            room -= min(int(B[k + 1]), q_max) - int(B[k])
+        return out
+
+    base = takes(order)
+    gap = math.inf
+    for r in range(len(order) - 1):
+        sw = order[:r] + [order[r + 1], order[r]] + order[r + 2:]
+        if takes(sw) != base:
+            gap = min(gap, abs(float(S_row[order[r]]) - float(S_row[order[r + 1]])))
+    return gap
+
+
+def test_block_form_cut_gap_by_trial_and_with_planted_ties():
+    """cut_gap of plan_blocks_head (the near-tie count of the row-block form, Alg. 1's Argsort tie rule):
+    equal to the gap found by exchanging adjacent ranks one pair at a time; exactly 0 where two identical
+    key-chunk vectors sit at a block's cut-off and positive elsewhere; never below the row form's gap
+    when the blocks coincide with the chunks (the block's list is its last row's list)."""
+    rng = np.random.default_rng(21)
+    L, D, B_r, N_b = 420, 8, 12, 45
+    B = rand_boundaries(rng, L, 3, 20)
+    N_c = len(B) - 1
+    Q = rng.standard_normal((1, L, D)).astype(np.float32)
+    Kc = rng.standard_normal((N_c, D))
+    Qb = oracle.pool_blocks(Q, B_r)[0]
+    N_r = Qb.shape[0]
+    take, gap = oracle.plan_blocks_head(Qb, Kc, B, B_r, N_b)
+    finite = 0
+    for i in range(N_r):
+        q_max = min((i + 1) * B_r, L)
+        want = _swap_gap(_score_row(Qb[i], Kc), B, q_max, N_b)
+        assert gap[i] == want, (i, gap[i], want)
+        finite += math.isfinite(want)
+    assert finite > N_r // 2 and (gap > 0).all()
+    assert math.isinf(gap[0]) and take[0].sum() == min(N_b, B_r)     # the first block takes all it sees: no cut-off
+    # plant a duplicate: chunks 2 and 3 get the same vector, so they are always adjacent in the ranking
+    Kc2 = Kc.copy()
+    Kc2[3] = Kc2[2]
+    take2, gap2 = oracle.plan_blocks_head(Qb, Kc2, B, B_r, N_b)
+    zeros = 0
+    for i in range(N_r):
+        q_max = min((i + 1) * B_r, L)
+        S_row = _score_row(Qb[i], Kc2)
+        assert gap2[i] == _swap_gap(S_row, B, q_max, N_b)
+        if B[3] < q_max:
+            pi = [int(k) for k in oracle.rank(S_row) if B[k] < q_max]
+            assert pi[pi.index(2) + 1] == 3                                # tie -> lower id first
+            len2, len3 = (min(int(B[k + 1]), q_max) - int(B[k]) for k in (2, 3))
+            at_cut = take2[i, 2] > 0 and not (take2[i, 2] == len2 and take2[i, 3] == len3)
+            assert (gap2[i] == 0.0) == at_cut
+            zeros += at_cut
+        else:
+            assert gap2[i] > 0
+    assert zeros > 0
+    # blocks that coincide with the chunks: the pairs that matter to the block's (= last row's) list are
+    # among those that matter to some row of the chunk
+    B_u = np.arange(0, 40 * B_r + 1, B_r, dtype=np.int32)
+    Qu = rng.standard_normal((40, D))
+    Ku = rng.standard_normal((40, D))
+    Ku[7] = Ku[6]
+    zeros = 0
+    for nb in (7, 30, 100):
+        _, _, gap_rows = oracle.plan_head(Qu, Ku, B_u, nb)
+        _, gap_blocks = oracle.plan_blocks_head(Qu, Ku, B_u, B_r, nb)
+        assert (gap_blocks >= gap_rows).all()
+        zeros += int((gap_blocks == 0).sum())
+    assert zeros > 0
+
+
 def test_block_form_with_a_budget_of_everything_is_dense_causal_attention():
     rng = np.random.default_rng(13)
     H_q, H_kv, L, D, B_r = 4, 2, 45, 8, 7
