@@ -136,8 +136,9 @@ typedef struct {
  *        t < rem and B[k] + t <= i      if pos = 3 (the block's list, causal mask per token)
  *      Only chunks some row of l takes a token from are listed.
  *   off_tiles  int32[T1][2]  row tiles of one head: (chunk l, first row), rows
- *                            [row, min(row + 128, B[l+1])); first the T_big tiles of
- *                            more than 64 rows, then the others, each group by row
+ *                            [row, min(row + 128, B[l+1])), listed by height: tiles of
+ *                            more than 96 rows, then 65..96, 33..64, at most 32 rows
+ *                            (the first T_big have more than 64), each class by row
  */
 #define DHSA_PLAN_MAGIC 0x41534844
 #define DHSA_PLAN_VERSION 2

@@ -34,6 +34,8 @@
 // Query groups: a tile's rows belong to one query group l = rows [RB[l], RB[l+1]):
 // a chunk (RB = B), or a fixed row block of Alg. 1 as printed, whose listed keys
 // are masked causally per token like the keys of a row's own chunk.
+#include <stddef.h>
+
 #include "dhsa_internal.h"
 
 namespace dhsa {
@@ -93,9 +95,9 @@ struct AttnSmem {
 // each XCD has its own L2.  `act` kv-heads (1, 2, 4 or 8) are worked on at a
 // time, each by 8 / act XCDs: act = 8 gives every XCD its own kv-head (best L2
 // reuse of the K/V slabs), smaller values keep fewer K/V slabs live at once
-// (they then fit the memory-side cache).  Within a kv-head, row tiles are
-// issued from the end of the sequence (most keys) to the start, the query heads
-// of the group innermost.  act = 0: plain order.
+// (they then fit the memory-side cache).  Within a kv-head the query heads of
+// the group are innermost; *tile is the tile's position in the order of issue
+// (0 = first), which the kernel maps to a row tile.  act = 0: plain order.
 __device__ __forceinline__ void decode_block(int act, int b, int H_q, int G, int T1, int *h, int *tile) {
     if (act > 0) {
         const int per = act * G * T1;          // workgroups per set of `act` kv-heads
@@ -103,11 +105,11 @@ __device__ __forceinline__ void decode_block(int act, int b, int H_q, int G, int
         const int x = r & 7;
         const int kv = p * act + (x & (act - 1));
         const int idx = (r >> 3) * (8 / act) + x / act;
-        *tile = T1 - 1 - idx / G;
+        *tile = idx / G;
         *h = kv * G + idx % G;
         return;
     }
-    *tile = T1 - 1 - b / H_q;
+    *tile = b / H_q;
     *h = b % H_q;
 }
 
@@ -118,44 +120,131 @@ static int attn_order(int want, int H_kv, int G, int T1) {
     return 0;
 }
 
-template <int D, bool PAR>
-__global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, int T, const uint16_t *__restrict__ Q,
-                                                      const uint16_t *__restrict__ K,
-                                                      const uint16_t *__restrict__ V, uint16_t *__restrict__ O,
-                                                      int H_q, int G, int mode,
-                                                      float scale_log2e, int64_t qs_h, int64_t qs_l,
-                                                      int64_t ks_h, int64_t ks_l, int64_t vs_h, int64_t vs_l,
-                                                      int64_t os_h, int64_t os_l) {
+// ---------------------------------------------------------------------------
+// Key lists and loads, shared by the two kernels below (they use the same names
+// for the variables these macros touch: sm, lane, tid, wave_u, total, v_lo, v_hi,
+// b_l, row0, nrows, k_row_bytes, v_row_bytes, off_slot_wr, off_slot_rd, lds_K,
+// lds_V, Kg8, Vg8, ld_piece_bytes_k / _v, ko_lo, ko_hi, vo, KPT, kTile).
+// ---------------------------------------------------------------------------
+// Segment table of the batch of plan entries [e0, e0 + kSegB) for this tile: per entry the first
+// packed position of its keys (sm.seg_start, an exclusive scan of the most tokens any row of the
+// tile takes from the entry; for the row-block form keys past the tile's last row are dropped),
+// the chunk's first token, pos and rem.  Defines `total`, the packed keys of the batch.  Contains
+// block barriers.
+#define DHSA_SEGMENT_TABLE(e0) \
+    int n_e = 0; \
+    if (e0 + tid < E) { \
+        const int w0 = ent[2 * (e0 + tid)], rem = ent[2 * (e0 + tid) + 1]; \
+        const int k = w0 & kChunkMask, pos = w0 >> kPosShift; \
+        const int b0 = pv.B[k]; \
+        n_e = entry_take(pos, rem, pv.B[k + 1] - b0, pos == 1 ? v_hi : v_lo); \
+        if (pos == 3) { \
+            const int vis = row0 + nrows - b0; \
+            n_e = vis < n_e ? (vis > 0 ? vis : 0) : n_e; \
+        } \
+        sm.seg_b0[tid] = b0; \
+        sm.seg_pos[tid] = pos; \
+        sm.seg_rem[tid] = rem; \
+    } \
+    int total; \
+    const int start = block_excl_scan(n_e, sm.s_wave, &total); \
+    sm.seg_start[tid] = start; \
+    if (tid < 16) sm.seg_start[kSegB + tid] = total; \
+    __syncthreads();
+
+// one wave: packed position -> (row offsets, lo, hi) of tile n.  The segment of a
+// position is found with two 16-way steps over the sorted segment starts.
+#define DHSA_MAKE_META(n)                                                                       \
+    {                                                                                           \
+        const int buf_ = (n) & 7;                                                               \
+        int x_ = (n) * kKT + lane;                                                              \
+        const bool pad_ = x_ >= total;                                                          \
+        if (pad_) x_ = total - 1;                                                               \
+        int c_ = -1;                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) c_ += (sm.seg_start[16 * i_] <= x_);  \
+        int f_ = -1;                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                      \
+            const int4 q_ = *reinterpret_cast<const int4 *>(&sm.seg_start[16 * c_ + 4 * i_]);   \
+            f_ += (q_.x <= x_) + (q_.y <= x_) + (q_.z <= x_) + (q_.w <= x_);                    \
+        }                                                                                       \
+        const int seg_ = 16 * c_ + f_;                                                          \
+        const int t_ = x_ - sm.seg_start[seg_];                                                 \
+        const int pos_ = sm.seg_pos[seg_];                                                      \
+        const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
+        /* key j is at or below row i  <=>  j - b_l < v: the group's own chunk (pos 1,   */     \
+        /* j - b_l = t) and every listed key of the row-block form (pos 3) */                   \
+        int lo_ = (pos_ & 1) ? ((int)j_ > b_l ? (int)j_ - b_l : 0) : 0;                         \
+        int hi_ = (pos_ == 2) ? sm.seg_rem[seg_] - t_ : kIntMax;                                \
+        if (pad_) { lo_ = kIntMax; hi_ = kIntMax; }                                             \
+        sm.key_koff[buf_][off_slot_wr] = j_ * k_row_bytes;                                      \
+        sm.key_voff[buf_][off_slot_wr] = j_ * v_row_bytes;                                      \
+        sm.key_lo[buf_][lane] = lo_;                                                            \
+        sm.key_hi[buf_][lane] = hi_;                                                            \
+        const unsigned long long any_ = __ballot((lo_ >= v_lo) || (hi_ <= v_hi));               \
+        if (lane == 0) sm.flags[buf_] = any_ != 0ull;                                           \
+    }
+
+// fetch this lane's row offsets of tile n into registers (windows c0..c1-1)
+#define DHSA_OFFS(dst, off_tab, n, c0, c1)                                                      \
+    _Pragma("unroll") for (int c = c0; c < c1; ++c) dst[c] = sm.off_tab[(n) & 7][off_slot_rd + c];
+// issue the global -> LDS loads of windows c0..c1-1 of the K (or V) rows of tile n,
+// row offsets taken from registers
+#define DHSA_GLOAD(lds_base, offs, base8, piece_bytes, n, c0, c1)                               \
+    {                                                                                           \
+        const unsigned dst_ = lds_base + (((n) & 1) * kTile + wave_u * 512) * 2;                \
+        _Pragma("unroll") for (int c = c0; c < c1; ++c)                                         \
+            load16_to_lds(base8, offs[c] + piece_bytes, dst_ + c * 4096);                       \
+    }
+#define DHSA_LOAD_K_LO(n) DHSA_GLOAD(lds_K, ko_lo, Kg8, ld_piece_bytes_k, n, 0, KPT / 2)      /* keys 0..31  */
+#define DHSA_LOAD_K_HI(n) DHSA_GLOAD(lds_K, ko_hi, Kg8, ld_piece_bytes_k, n, KPT / 2, KPT)    /* keys 32..63 */
+#define DHSA_LOAD_V(n) DHSA_GLOAD(lds_V, vo, Vg8, ld_piece_bytes_v, n, 0, KPT)
+#define DHSA_LOAD_V_LO(n) DHSA_GLOAD(lds_V, vo, Vg8, ld_piece_bytes_v, n, 0, KPT / 2)
+#define DHSA_LOAD_V_HI(n) DHSA_GLOAD(lds_V, vo, Vg8, ld_piece_bytes_v, n, KPT / 2, KPT)
+
+
+// Everything the tile bodies need beside the plan (kernel arguments, passed on by reference).
+struct AttnArgs {
+    const uint16_t *Q, *K, *V;
+    uint16_t *O;
+    int G;
+    float scale_log2e;
+    int64_t qs_h, qs_l, ks_h, ks_l, vs_h, vs_l, os_h, os_l;
+};
+
+// One row tile of more than 64 rows (any tile of up to 128 rows is handled correctly): see the
+// header of this file.
+template <int D>
+__device__ __forceinline__ void attn_tile_32(AttnSmem<D> &sm, const PlanView &pv, const AttnArgs &a, const int h,
+                                             const int tile) {
     using Smem = AttnSmem<D>;
     constexpr int OPR = D / 8;          // 16-byte pieces per row
     constexpr int KPT = OPR / 4;        // load instructions per wave per tile (K and V each)
     constexpr int NS = D / 16;          // MFMA k-steps of Q K^T
     constexpr int NDB = D / 32;         // 32-wide output column blocks
     constexpr int kTile = Smem::kTile;
-    __shared__ Smem sm;
+    const uint16_t *__restrict__ Q = a.Q;
+    const uint16_t *__restrict__ K = a.K;
+    const uint16_t *__restrict__ V = a.V;
+    uint16_t *__restrict__ O = a.O;
+    const int G = a.G;
+    const float scale_log2e = a.scale_log2e;
+    const int64_t qs_h = a.qs_h, qs_l = a.qs_l, ks_h = a.ks_h, ks_l = a.ks_l, vs_h = a.vs_h, vs_l = a.vs_l,
+                  os_h = a.os_h, os_l = a.os_l;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform copy
     const int lr = lane & 31, g2 = lane >> 5;
 
-    int h, tile;
-    decode_block(mode, blockIdx.x, H_q, G, T, &h, &tile);
-    tile += tile0;   // this launch covers tiles [tile0, tile0 + T) of the plan's table
     const int g = h / G;
     const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];   // query group, first row
     const int b_l = pv.RB[l];
     const int rows_left = pv.RB[l + 1] - row0;
     const int nrows = rows_left < kRowTile ? rows_left : kRowTile;
     const int v_lo = row0 + 1 - b_l, v_hi = v_lo + nrows - 1;
-    // Wave roles (PAR = false / true is chosen per launch: the plan lists the tiles
-    // of more than 64 rows first).  Tiles of more than 64 rows: wave = one 32-row block (rotated per
-    // workgroup so that the waves left without rows do not always sit on the same
-    // SIMD), both 32-key blocks of every key tile.  Tiles of at most 64 rows: two
-    // waves per row block, each taking ONE of the two 32-key blocks of every key
-    // tile ("key parity" kbw); their partial softmax states are merged at the end.
-    constexpr bool par = PAR;
-    const int rb = par ? (wave & 1) : ((wave + (blockIdx.x >> 3)) & 3);
-    const int kbw = par ? (wave >> 1) : 0;
+    // Wave = one 32-row block of the tile (rotated per workgroup so that the waves left without
+    // rows do not always sit on the same SIMD), every 32-key block of the key list.
+    const int rb = (wave + (blockIdx.x >> 3)) & 3;
+    constexpr int kbw = 0;
     const bool wave_live = rb * 32 < nrows;
     const int v_i = v_lo + rb * 32 + lr;  // this lane's query row (may be a padding row)
 
@@ -197,7 +286,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     // swizzle(row) (the rows of one lane are 16 or 32 apart: same swizzle)
     constexpr int RPW = 64 / OPR;                                     // rows per window
     const int ld_row0 = wave * RPW + lane / OPR;
-    const unsigned ld_piece_bytes = 16u * ((lane % OPR) ^ piece_swizzle(ld_row0, OPR));
+    const unsigned ld_piece_bytes_k = 16u * ((lane % OPR) ^ piece_swizzle(ld_row0, OPR));
+    const unsigned ld_piece_bytes_v = ld_piece_bytes_k;
     // the rows one lane fetches for a tile are ld_row0 + c RSTR, c = 0 .. KPT-1; the offset of
     // key row r sits in slot (r % RSTR) KPT + r / RSTR of the tile's offset table
     constexpr int RSTR = 4 * RPW;
@@ -226,78 +316,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     const char *const smV8 = reinterpret_cast<const char *>(sm.V);
 
     for (int e0 = 0; e0 < E; e0 += kSegB) {
-        // ---- segment table of this batch of plan entries ----
-        int n_e = 0;
-        if (e0 + tid < E) {
-            const int w0 = ent[2 * (e0 + tid)], rem = ent[2 * (e0 + tid) + 1];
-            const int k = w0 & kChunkMask, pos = w0 >> kPosShift;
-            const int b0 = pv.B[k];
-            // most tokens any row of the tile takes from this chunk
-            n_e = entry_take(pos, rem, pv.B[k + 1] - b0, pos == 1 ? v_hi : v_lo);
-            if (pos == 3) {   // row-block form: keys past the tile's last row are masked for every row
-                const int vis = row0 + nrows - b0;
-                n_e = vis < n_e ? (vis > 0 ? vis : 0) : n_e;
-            }
-            sm.seg_b0[tid] = b0;
-            sm.seg_pos[tid] = pos;
-            sm.seg_rem[tid] = rem;
-        }
-        int total;
-        const int start = block_excl_scan(n_e, sm.s_wave, &total);
-        sm.seg_start[tid] = start;                 // entries past the last segment hold `total`
-        if (tid < 16) sm.seg_start[kSegB + tid] = total;
-        __syncthreads();
+        DHSA_SEGMENT_TABLE(e0);
         const int ntiles = (total + kKT - 1) / kKT;
         if (ntiles == 0) continue;
-
-// one wave: packed position -> (row offsets, lo, hi) of tile n.  The segment of a
-// position is found with two 16-way steps over the sorted segment starts.
-#define DHSA_MAKE_META(n)                                                                       \
-    {                                                                                           \
-        const int buf_ = (n) & 7;                                                               \
-        int x_ = (n) * kKT + lane;                                                              \
-        const bool pad_ = x_ >= total;                                                          \
-        if (pad_) x_ = total - 1;                                                               \
-        int c_ = -1;                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) c_ += (sm.seg_start[16 * i_] <= x_);  \
-        int f_ = -1;                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                      \
-            const int4 q_ = *reinterpret_cast<const int4 *>(&sm.seg_start[16 * c_ + 4 * i_]);   \
-            f_ += (q_.x <= x_) + (q_.y <= x_) + (q_.z <= x_) + (q_.w <= x_);                    \
-        }                                                                                       \
-        const int seg_ = 16 * c_ + f_;                                                          \
-        const int t_ = x_ - sm.seg_start[seg_];                                                 \
-        const int pos_ = sm.seg_pos[seg_];                                                      \
-        const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \
-        /* key j is at or below row i  <=>  j - b_l < v: the group's own chunk (pos 1,   */     \
-        /* j - b_l = t) and every listed key of the row-block form (pos 3) */                   \
-        int lo_ = (pos_ & 1) ? ((int)j_ > b_l ? (int)j_ - b_l : 0) : 0;                         \
-        int hi_ = (pos_ == 2) ? sm.seg_rem[seg_] - t_ : kIntMax;                                \
-        if (pad_) { lo_ = kIntMax; hi_ = kIntMax; }                                             \
-        sm.key_koff[buf_][off_slot_wr] = j_ * k_row_bytes;                                      \
-        sm.key_voff[buf_][off_slot_wr] = j_ * v_row_bytes;                                      \
-        sm.key_lo[buf_][lane] = lo_;                                                            \
-        sm.key_hi[buf_][lane] = hi_;                                                            \
-        const unsigned long long any_ = __ballot((lo_ >= v_lo) || (hi_ <= v_hi));               \
-        if (lane == 0) sm.flags[buf_] = any_ != 0ull;                                           \
-    }
-
-// fetch this lane's row offsets of tile n into registers (windows c0..c1-1)
-#define DHSA_OFFS(dst, off_tab, n, c0, c1)                                                      \
-    _Pragma("unroll") for (int c = c0; c < c1; ++c) dst[c] = sm.off_tab[(n) & 7][off_slot_rd + c];
-// issue the global -> LDS loads of windows c0..c1-1 of the K (or V) rows of tile n,
-// row offsets taken from registers
-#define DHSA_GLOAD(lds_base, offs, base8, n, c0, c1)                                            \
-    {                                                                                           \
-        const unsigned dst_ = lds_base + (((n) & 1) * kTile + wave_u * 512) * 2;                \
-        _Pragma("unroll") for (int c = c0; c < c1; ++c)                                         \
-            load16_to_lds(base8, offs[c] + ld_piece_bytes, dst_ + c * 4096);                    \
-    }
-#define DHSA_LOAD_K_LO(n) DHSA_GLOAD(lds_K, ko_lo, Kg8, n, 0, KPT / 2)      /* keys 0..31  */
-#define DHSA_LOAD_K_HI(n) DHSA_GLOAD(lds_K, ko_hi, Kg8, n, KPT / 2, KPT)    /* keys 32..63 */
-#define DHSA_LOAD_V(n) DHSA_GLOAD(lds_V, vo, Vg8, n, 0, KPT)
-#define DHSA_LOAD_V_LO(n) DHSA_GLOAD(lds_V, vo, Vg8, n, 0, KPT / 2)
-#define DHSA_LOAD_V_HI(n) DHSA_GLOAD(lds_V, vo, Vg8, n, KPT / 2, KPT)
 
 // S^T of one 32-key block whose K rows start at element offset kb_off of the
 // buffer k_off points into: keys = MFMA rows, this lane's query row = column lr
@@ -396,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
         unsigned ko_lo[KPT], ko_hi[KPT], vo[KPT];   // row offsets of the loads this lane issues next
         if (wave < ntiles) DHSA_MAKE_META(wave);   // key lists of tiles 0..3
         __syncthreads();
-        if constexpr (!PAR) {
+        {
         // ================= tiles of more than 64 rows =================
         // ---- prologue: K(0), V(0), lower half of K(1) in LDS; S(0, block 0) ----
         DHSA_OFFS(ko_lo, key_koff, 0, 0, KPT / 2);
@@ -478,114 +499,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
             v_base_e -= 2 * kTile;
             v_base_o -= 2 * kTile;
         }
-        } else {
-        // ================= tiles of at most 64 rows: one 32-key block per wave and tile =================
-        // ---- prologue: K(0), V(0), K(1) in LDS; S(0, own block) ----
-        DHSA_OFFS(ko_lo, key_koff, 0, 0, KPT / 2);
-        DHSA_OFFS(ko_hi, key_koff, 0, KPT / 2, KPT);
-        DHSA_OFFS(vo, key_voff, 0, 0, KPT);
-        DHSA_LOAD_K_LO(0);
-        DHSA_LOAD_K_HI(0);
-        DHSA_LOAD_V(0);
-        if (ntiles > 1) {
-            DHSA_OFFS(ko_lo, key_koff, 1, 0, KPT / 2);
-            DHSA_OFFS(ko_hi, key_koff, 1, KPT / 2, KPT);
-            DHSA_LOAD_K_LO(1);
-            DHSA_LOAD_K_HI(1);
         }
-        const int fl_0 = __builtin_amdgcn_readfirstlane(sm.flags[0]);
-        __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
-        if (wave_live) {
-            DHSA_QK(0, s_a);
-            DHSA_MASK(0, kbw, s_a, fl_0);
-            if (e0 == 0) { float mx0; DHSA_ROWMAX(s_a, mx0); m_ref = fmaxf(m_ref, mx0); }   // reference = row maxima of this wave's first block
-#pragma unroll
-            for (int s = 0; s < NS; ++s) k_off[s] += 2 * kTile;   // K offsets run one tile ahead of V offsets
-        }
-        __syncthreads();                      // K(0) may be overwritten from here on
-
-        // ---- tile n (all but the last): softmax and PV of this wave's block (scores in s_a)
-        // while the matrix unit computes the scores of its block of tile n+1 (into s_b) ----
-        int n = 0;
-        for (; n + 1 < ntiles; ++n) {
-            DHSA_OFFS(ko_lo, key_koff, n + 2, 0, KPT / 2);
-            DHSA_OFFS(ko_hi, key_koff, n + 2, KPT / 2, KPT);
-            DHSA_OFFS(vo, key_voff, n + 1, 0, KPT);
-            const int fl_next = __builtin_amdgcn_readfirstlane(sm.flags[(n + 1) & 7]);
-            if (n + 2 < ntiles) { DHSA_LOAD_K_LO(n + 2); DHSA_LOAD_K_HI(n + 2); }   // over K(n)
-            DHSA_LOAD_V(n + 1);                                                    // over V(n-1)
-            if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
-            if (wave_live) {
-                bf16x8 pf[2];
-                DHSA_QK(0, s_b);
-                DHSA_EXP(s_a, pf);
-                DHSA_PV(0, pf);
-                DHSA_MASK(n + 1, kbw, s_b, fl_next);
-                s_a = s_b;
-#pragma unroll
-                for (int s = 0; s < NS; ++s) k_off[s] -= toggle;
-                v_base_e += toggle;
-                v_base_o += toggle;
-                toggle = -toggle;
-            }
-            __builtin_amdgcn_s_waitcnt(0x0f70);
-            __syncthreads();
-        }
-        if (wave_live) {                          // last tile of the batch
-            bf16x8 pf[2];
-            DHSA_EXP(s_a, pf);
-            DHSA_PV(0, pf);
-        }
-        __syncthreads();                          // LDS is reused by the next batch / the merge
-        if (wave_live) {                          // leave the offsets at buffer 0 for the next batch
-            if (ntiles & 1) {
-#pragma unroll
-                for (int s = 0; s < NS; ++s) k_off[s] -= 2 * kTile;
-            } else {
-                v_base_e -= 2 * kTile;
-                v_base_o -= 2 * kTile;
-            }
-        }
-        }
-#undef DHSA_MAKE_META
-#undef DHSA_OFFS
-#undef DHSA_GLOAD
-#undef DHSA_LOAD_K_LO
-#undef DHSA_LOAD_K_HI
-#undef DHSA_LOAD_V
-#undef DHSA_LOAD_V_LO
-#undef DHSA_LOAD_V_HI
 #undef DHSA_QK
 #undef DHSA_MASK
 #undef DHSA_ROWMAX
 #undef DHSA_EXP
 #undef DHSA_PV
-    }
-
-    // ---- key-parity tiles: fold the state of the wave that took the odd blocks into its partner ----
-    if constexpr (PAR) {
-        float *xch = reinterpret_cast<float *>(sm.K) + rb * (NDB * 16 + 2) * 64 + lane;   // [slot][lane]
-        if (wave_live && kbw == 1) {
-            xch[0] = m_ref;
-            xch[64] = l_run;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) xch[(2 + db * 16 + x) * 64] = oacc[db][x];
-        }
-        __syncthreads();
-        if (wave_live && kbw == 0) {
-            const float m1 = xch[0], l1 = xch[64];
-            const float mm = fmaxf(m_ref, m1);
-            const float a0 = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mm) * scale_log2e);
-            const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - mm) * scale_log2e);
-            l_run = l_run * a0 + l1 * a1;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) oacc[db][x] = oacc[db][x] * a0 + xch[(2 + db * 16 + x) * 64] * a1;
-        }
     }
 
     // ---- epilogue: normalise, round to bf16, store ----
@@ -608,24 +527,402 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, int tile0, in
     }
 }
 
+// ---------------------------------------------------------------------------
+// Row tiles of at most 96 rows: 16-row MFMA blocks (v_mfma_f32_16x16x32_bf16).
+//
+// The tile's rows are cut into two row groups of 16 RW rows (RW = 1, 2, 3: tiles
+// of at most 32, 64, 96 rows); a wave owns one row group and ONE of the two
+// 32-key blocks of every 64-key tile ("key parity" kbw), so all four waves work
+// whatever the tile's height, and the two waves of a row group merge their
+// partial softmax states at the end.  A K or V fragment read from LDS serves the
+// RW row blocks of the wave (at RW = 3 a third less LDS traffic per product
+// than one 32-row block per wave).
+//
+// Lane l = 16 q + n of a wave.  S^T block = K (16 keys x 32 d) Q^T (32 d x 16
+// rows): the lane holds, per row block r and key half kh, the scores of row n of
+// the block against keys 16 kh + 4 q + {0..3} of the wave's key block -- 8 keys
+// of ONE query row per row block, which after the exponential are exactly the B
+// operand of O^T (16 d x 16 rows) += V^T (16 d x 32 keys) P^T (32 keys x 16
+// rows) when the contraction index 8 q + i is read as key 4 q + i (i < 4) or
+// 16 + 4 q + i - 4: the V^T operand is fetched in that key order with two
+// transpose reads.  The four lanes of a row (same n) share the exponent
+// reference; their row sums are added at the very end.
+//
+// K rows are swizzled by row & 15 here (16-byte column reads of 16 rows x 4
+// pieces; the swizzle of the 32-row kernel would make two lanes of a bank group
+// collide), V rows as in the kernel above.  Loads, key lists and the pipeline
+// (scores of this wave's block of tile n + 1 on the matrix unit while the block
+// of tile n is exponentiated) are those of the key-parity path above.
+// ---------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int piece_swizzle_k16(int r, int pieces_per_row) {
+    return pieces_per_row == 16 ? (r & 15) : piece_swizzle(r, pieces_per_row);
+}
+
+template <int D, int RW>
+__device__ __forceinline__ void attn_tile_16(AttnSmem<D> &sm, const PlanView &pv, const AttnArgs &a, const int h,
+                                             const int tile) {
+    using Smem = AttnSmem<D>;
+    constexpr int OPR = D / 8;          // 16-byte pieces per row
+    constexpr int KPT = OPR / 4;        // load instructions per wave per tile (K and V each)
+    constexpr int NT = D / 32;          // MFMA k-steps of K Q^T
+    constexpr int NJ = D / 16;          // 16-wide blocks of the head dimension (rows of O^T)
+    constexpr int kTile = Smem::kTile;
+    const uint16_t *__restrict__ Q = a.Q;
+    const uint16_t *__restrict__ K = a.K;
+    const uint16_t *__restrict__ V = a.V;
+    uint16_t *__restrict__ O = a.O;
+    const int G = a.G;
+    const float scale_log2e = a.scale_log2e;
+    const int64_t qs_h = a.qs_h, qs_l = a.qs_l, ks_h = a.ks_h, ks_l = a.ks_l, vs_h = a.vs_h, vs_l = a.vs_l,
+                  os_h = a.os_h, os_l = a.os_l;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int n16 = lane & 15, q = lane >> 4;
+
+    const int g = h / G;
+    const int l = pv.tiles[2 * tile], row0 = pv.tiles[2 * tile + 1];
+    const int b_l = pv.RB[l];
+    const int rows_left = pv.RB[l + 1] - row0;
+    const int nrows = rows_left < 32 * RW ? rows_left : 32 * RW;   // only tiles of <= 32 RW rows come here
+    const int v_lo = row0 + 1 - b_l, v_hi = v_lo + nrows - 1;
+    const int rg = wave & 1, kbw = wave >> 1;        // row group, key parity
+    const int rbase = rg * 16 * RW;
+    const bool wave_live = rbase < nrows;
+
+    const char *Kg8 = reinterpret_cast<const char *>(K + (int64_t)g * ks_h);
+    const char *Vg8 = reinterpret_cast<const char *>(V + (int64_t)g * vs_h);
+    const unsigned k_row_bytes = (unsigned)ks_l * 2u, v_row_bytes = (unsigned)vs_l * 2u;
+
+    // Q fragments (B operand of K Q^T): row n of row block r, d = 32 t + 8 q .. + 7.  Padding rows
+    // get q = 0 and, through a huge exponent reference, p = 0.
+    bf16x8 qf[RW][NT];
+    int v_i[RW];
+    float m_ref[RW], l_run[RW];
+    f32x4 oacc[RW][NJ];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int rr = rbase + 16 * r + n16;
+        const bool pad_row = rr >= nrows;
+        v_i[r] = v_lo + rr;
+        const uint16_t *qp = Q + (int64_t)h * qs_h + (int64_t)(row0 + (pad_row ? nrows - 1 : rr)) * qs_l + 8 * q;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            qf[r][t] = *reinterpret_cast<const bf16x8 *>(qp + 32 * t);
+            if (pad_row) qf[r][t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+        m_ref[r] = pad_row ? 1e30f : -INFINITY;
+        l_run[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) oacc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int E = pv.count[(int64_t)h * pv.N_q + l];
+    const int32_t *ent = pv.entries + ((int64_t)h * pv.N_q + l) * pv.stride * 2;
+
+    // staging (as in the kernel above; K with its own swizzle)
+    constexpr int RPW = 64 / OPR;
+    const int ld_row0 = wave * RPW + lane / OPR;
+    const unsigned ld_piece_bytes_k = 16u * ((lane % OPR) ^ piece_swizzle_k16(ld_row0, OPR));
+    const unsigned ld_piece_bytes_v = 16u * ((lane % OPR) ^ piece_swizzle(ld_row0, OPR));
+    constexpr int RSTR = 4 * RPW;
+    const int off_slot_wr = (lane % RSTR) * KPT + lane / RSTR;
+    const int off_slot_rd = ld_row0 * KPT;
+    const unsigned lds_K = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.K;
+    const unsigned lds_V = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)sm.V;
+    // K fragment of k-step t: key row kbw 32 + 16 kh + n, logical piece 4 t + q (byte offsets; kh by immediate)
+    int k_off[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        k_off[t] = 2 * (kbw * 32 + n16) * D + 16 * ((4 * t + q) ^ piece_swizzle_k16(n16, OPR));
+    // V^T fragment of head-dimension block j: the 16 lanes of group q read keys 4 q + rho (rho = n >> 2),
+    // four lanes per key covering d = 16 j + 4 (n & 3) .. + 3; the transpose read hands lane n element
+    // d = 16 j + n of the four keys
+    int v_off[NJ];
+    {
+        const int key = 4 * q + (n16 >> 2), c = n16 & 3;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            v_off[j] = 2 * (kbw * 32 + key) * D + 16 * ((2 * j + (c >> 1)) ^ piece_swizzle(key, OPR)) + 8 * (c & 1);
+    }
+    const char *const smK8 = reinterpret_cast<const char *>(sm.K);
+    const char *const smV8 = reinterpret_cast<const char *>(sm.V);
+
+    for (int e0 = 0; e0 < E; e0 += kSegB) {
+        DHSA_SEGMENT_TABLE(e0);
+        const int ntiles = (total + kKT - 1) / kKT;
+        if (ntiles == 0) continue;
+
+// S^T of this wave's 32-key block of the K buffer k_off points into, all row blocks
+#define DHSA_QK16(sacc)                                                                         \
+    {                                                                                           \
+        _Pragma("unroll") for (int kh = 0; kh < 2; ++kh) {                                      \
+            _Pragma("unroll") for (int r = 0; r < RW; ++r) sacc[r][kh] = f32x4{0.f, 0.f, 0.f, 0.f}; \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                    \
+                const bf16x8 kf_ = *reinterpret_cast<const bf16x8 *>(smK8 + k_off[t] + kh * 32 * D); \
+                _Pragma("unroll") for (int r = 0; r < RW; ++r)                                  \
+                    sacc[r][kh] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf_, qf[r][t], sacc[r][kh], 0, 0, 0); \
+            }                                                                                   \
+        }                                                                                       \
+    }
+
+#define DHSA_MASK16(n, sacc, flag)                                                              \
+    {                                                                                           \
+        if (flag) {                                                                             \
+            _Pragma("unroll") for (int kh = 0; kh < 2; ++kh) {                                  \
+                const int key_ = kbw * 32 + kh * 16 + 4 * q;                                    \
+                const int4 lo_ = *reinterpret_cast<const int4 *>(&sm.key_lo[(n) & 7][key_]);    \
+                const int4 hi_ = *reinterpret_cast<const int4 *>(&sm.key_hi[(n) & 7][key_]);    \
+                _Pragma("unroll") for (int r = 0; r < RW; ++r) {                                \
+                    sacc[r][kh][0] = ((v_i[r] > lo_.x) & (v_i[r] < hi_.x)) ? sacc[r][kh][0] : -INFINITY; \
+                    sacc[r][kh][1] = ((v_i[r] > lo_.y) & (v_i[r] < hi_.y)) ? sacc[r][kh][1] : -INFINITY; \
+                    sacc[r][kh][2] = ((v_i[r] > lo_.z) & (v_i[r] < hi_.z)) ? sacc[r][kh][2] : -INFINITY; \
+                    sacc[r][kh][3] = ((v_i[r] > lo_.w) & (v_i[r] < hi_.w)) ? sacc[r][kh][3] : -INFINITY; \
+                }                                                                               \
+            }                                                                                   \
+        }                                                                                       \
+    }
+
+// maximum over the 32 keys of the block for this lane's row of row block r (four lanes per row)
+#define DHSA_ROWMAX16(sa, mx)                                                                   \
+    {                                                                                           \
+        float m_ = fmaxf(fmaxf(sa[0][0], sa[0][1]), fmaxf(sa[0][2], sa[0][3]));                 \
+        m_ = fmaxf(m_, fmaxf(fmaxf(sa[1][0], sa[1][1]), fmaxf(sa[1][2], sa[1][3])));            \
+        m_ = fmaxf(m_, __shfl_xor(m_, 16));                                                     \
+        mx = fmaxf(m_, __shfl_xor(m_, 32));                                                     \
+    }
+
+// P = exp2((S - m_ref) c) per row block, with the lazily moved exponent reference of the kernel above
+#define DHSA_EXP16(sacc, pf)                                                                    \
+    _Pragma("unroll") for (int r = 0; r < RW; ++r) {                                            \
+        float mc_ = (m_ref[r] == -INFINITY) ? 0.f : m_ref[r] * scale_log2e;                     \
+        float psum_ = 0.f;                                                                      \
+        _Pragma("unroll") for (int x = 0; x < 8; ++x) {                                         \
+            const float e_ = __builtin_amdgcn_exp2f(sacc[r][x >> 2][x & 3] * scale_log2e - mc_); \
+            psum_ += e_;                                                                        \
+            pf[r][x] = (__bf16)e_;                                                              \
+        }                                                                                       \
+        if (__any(!(psum_ < 1048576.f) || m_ref[r] == -INFINITY)) {                             \
+            float mx_;                                                                          \
+            DHSA_ROWMAX16(sacc[r], mx_);                                                        \
+            const float m_new_ = fmaxf(m_ref[r], mx_);                                          \
+            const float alpha_ = (m_ref[r] == -INFINITY) ? 0.f                                  \
+                                 : __builtin_amdgcn_exp2f((m_ref[r] - m_new_) * scale_log2e);   \
+            l_run[r] *= alpha_;                                                                 \
+            _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                      \
+                _Pragma("unroll") for (int x = 0; x < 4; ++x) oacc[r][j][x] *= alpha_;          \
+            m_ref[r] = m_new_;                                                                  \
+            mc_ = (m_ref[r] == -INFINITY) ? 0.f : m_ref[r] * scale_log2e;                       \
+            psum_ = 0.f;                                                                        \
+            _Pragma("unroll") for (int x = 0; x < 8; ++x) {                                     \
+                const float e_ = __builtin_amdgcn_exp2f(sacc[r][x >> 2][x & 3] * scale_log2e - mc_); \
+                psum_ += e_;                                                                    \
+                pf[r][x] = (__bf16)e_;                                                          \
+            }                                                                                   \
+        }                                                                                       \
+        l_run[r] += psum_;                                                                      \
+    }
+
+// O^T += V^T P^T for this wave's 32-key block of the V buffer v_off points into
+#define DHSA_PV16(pf)                                                                           \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                            \
+        union { s16x4 h[2]; bf16x8 v; } vf_;                                                    \
+        _Pragma("unroll") for (int kh = 0; kh < 2; ++kh)                                        \
+            vf_.h[kh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                                \
+                (s16x4 __attribute__((address_space(3))) *)(smV8 + v_off[j] + kh * 32 * D));    \
+        _Pragma("unroll") for (int r = 0; r < RW; ++r)                                          \
+            oacc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf_.v, pf[r], oacc[r][j], 0, 0, 0); \
+    }
+
+        f32x4 s_a[RW][2], s_b[RW][2];
+        int toggle = 2 * kTile;
+        unsigned ko_lo[KPT], ko_hi[KPT], vo[KPT];
+        if (wave < ntiles) DHSA_MAKE_META(wave);
+        __syncthreads();
+        // ---- prologue: K(0), V(0), K(1) in LDS; S(0, own block) ----
+        DHSA_OFFS(ko_lo, key_koff, 0, 0, KPT / 2);
+        DHSA_OFFS(ko_hi, key_koff, 0, KPT / 2, KPT);
+        DHSA_OFFS(vo, key_voff, 0, 0, KPT);
+        DHSA_LOAD_K_LO(0);
+        DHSA_LOAD_K_HI(0);
+        DHSA_LOAD_V(0);
+        if (ntiles > 1) {
+            DHSA_OFFS(ko_lo, key_koff, 1, 0, KPT / 2);
+            DHSA_OFFS(ko_hi, key_koff, 1, KPT / 2, KPT);
+            DHSA_LOAD_K_LO(1);
+            DHSA_LOAD_K_HI(1);
+        }
+        const int fl_0 = __builtin_amdgcn_readfirstlane(sm.flags[0]);
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+        __syncthreads();
+        if (wave_live) {
+            DHSA_QK16(s_a);
+            DHSA_MASK16(0, s_a, fl_0);
+            if (e0 == 0) {   // reference = row maxima of this wave's first block
+#pragma unroll
+                for (int r = 0; r < RW; ++r) { float mx0; DHSA_ROWMAX16(s_a[r], mx0); m_ref[r] = fmaxf(m_ref[r], mx0); }
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) k_off[t] += 2 * kTile;   // K offsets run one tile ahead of V offsets
+        }
+        __syncthreads();                      // K(0) may be overwritten from here on
+
+        int n = 0;
+        for (; n + 1 < ntiles; ++n) {
+            DHSA_OFFS(ko_lo, key_koff, n + 2, 0, KPT / 2);
+            DHSA_OFFS(ko_hi, key_koff, n + 2, KPT / 2, KPT);
+            DHSA_OFFS(vo, key_voff, n + 1, 0, KPT);
+            const int fl_next = __builtin_amdgcn_readfirstlane(sm.flags[(n + 1) & 7]);
+            if (n + 2 < ntiles) { DHSA_LOAD_K_LO(n + 2); DHSA_LOAD_K_HI(n + 2); }   // over K(n)
+            DHSA_LOAD_V(n + 1);                                                    // over V(n-1)
+            if ((n & 3) == 0 && n + 4 + wave < ntiles) DHSA_MAKE_META(n + 4 + wave);
+            if (wave_live) {
+                bf16x8 pf[RW];
+                DHSA_QK16(s_b);
+                DHSA_EXP16(s_a, pf);
+                DHSA_PV16(pf);
+                DHSA_MASK16(n + 1, s_b, fl_next);
+#pragma unroll
+                for (int r = 0; r < RW; ++r) { s_a[r][0] = s_b[r][0]; s_a[r][1] = s_b[r][1]; }
+#pragma unroll
+                for (int t = 0; t < NT; ++t) k_off[t] -= toggle;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) v_off[j] += toggle;
+                toggle = -toggle;
+            }
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+            __syncthreads();
+        }
+        if (wave_live) {                          // last tile of the batch
+            bf16x8 pf[RW];
+            DHSA_EXP16(s_a, pf);
+            DHSA_PV16(pf);
+        }
+        __syncthreads();                          // LDS is reused by the next batch / the merge
+        if (wave_live) {                          // leave the offsets at buffer 0 for the next batch
+            if (ntiles & 1) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) k_off[t] -= 2 * kTile;
+            } else {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) v_off[j] -= 2 * kTile;
+            }
+        }
+#undef DHSA_QK16
+#undef DHSA_MASK16
+#undef DHSA_ROWMAX16
+#undef DHSA_EXP16
+#undef DHSA_PV16
+    }
+
+    // ---- fold the state of the wave that took the odd key blocks into its partner ----
+    {
+        constexpr int SLOTS = RW * (2 + 4 * NJ);
+        // the exchange area starts at K and runs on into V, which follows it in AttnSmem; both are dead here
+        static_assert(offsetof(Smem, V) == sizeof(sm.K) && 2 * SLOTS * 64 * sizeof(float) <= sizeof(sm.K) + sizeof(sm.V),
+                      "merge scratch must fit K + V");
+        float *xch = reinterpret_cast<float *>(sm.K) + rg * SLOTS * 64 + lane;   // [slot][lane]
+        if (wave_live && kbw == 1) {
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                xch[(r * (2 + 4 * NJ)) * 64] = m_ref[r];
+                xch[(r * (2 + 4 * NJ) + 1) * 64] = l_run[r];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) xch[(r * (2 + 4 * NJ) + 2 + 4 * j + x) * 64] = oacc[r][j][x];
+            }
+        }
+        __syncthreads();
+        if (wave_live && kbw == 0) {
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                const float m1 = xch[(r * (2 + 4 * NJ)) * 64], l1 = xch[(r * (2 + 4 * NJ) + 1) * 64];
+                const float mm = fmaxf(m_ref[r], m1);
+                const float a0 = (m_ref[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref[r] - mm) * scale_log2e);
+                const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - mm) * scale_log2e);
+                l_run[r] = l_run[r] * a0 + l1 * a1;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        oacc[r][j][x] = oacc[r][j][x] * a0 + xch[(r * (2 + 4 * NJ) + 2 + 4 * j + x) * 64] * a1;
+            }
+        }
+    }
+
+    // ---- epilogue: normalise, round to bf16, store (lane: row n of each row block, d = 16 j + 4 q .. + 3) ----
+    if (wave_live && kbw == 0) {
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            float l_tot = l_run[r] + __shfl_xor(l_run[r], 16);
+            l_tot += __shfl_xor(l_tot, 32);
+            const int rr = rbase + 16 * r + n16;
+            if (rr < nrows) {
+                const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;   // no visible key (row-block form): zeros
+                uint16_t *op = O + (int64_t)h * os_h + (int64_t)(row0 + rr) * os_l + 4 * q;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    union { __bf16 b[4]; uint2 u; } pk;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) pk.b[x] = (__bf16)(oacc[r][j][x] * inv);
+                    *reinterpret_cast<uint2 *>(op + 16 * j) = pk.u;
+                }
+            }
+        }
+    }
+}
+
+// One launch per tile class (a kernel that holds all three bodies measured 3-10 % slower than
+// the sum of these).  CLS 0: tiles of more than 64 rows (table classes 0 and 1), 1: 33..64 rows,
+// 2: at most 32 rows.  Inside a launch tiles are issued from the end of the sequence (most keys)
+// to its start, so that the launch ends with the cheapest workgroups.
+template <int D, int CLS>
+__global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, AttnArgs a, int H_q, int mode, int tile0, int T) {
+    __shared__ AttnSmem<D> sm;
+    int h, pos;
+    decode_block(mode, blockIdx.x, H_q, a.G, T, &h, &pos);
+    const int tile = tile0 + T - 1 - pos;
+    if constexpr (CLS == 0) attn_tile_32<D>(sm, pv, a, h, tile);
+    else if constexpr (CLS == 1) attn_tile_16<D, 2>(sm, pv, a, h, tile);
+    else attn_tile_16<D, 1>(sm, pv, a, h, tile);
+}
+
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                             void *O, hipStream_t s) {
     const int want = 8;   // kv-heads in flight: one per XCD (other orders measured within 2 %)
-    const float c = p.scale * 1.4426950408889634f;
-#define DHSA_MFMA(DD, PAR, tile0, T)                                                                        \
-    {                                                                                                       \
+    AttnArgs a;
+    a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V; a.O = (uint16_t *)O;
+    a.G = p.G;
+    a.scale_log2e = p.scale * 1.4426950408889634f;
+    a.qs_h = p.qs_h; a.qs_l = p.qs_l; a.ks_h = p.ks_h; a.ks_l = p.ks_l;
+    a.vs_h = p.vs_h; a.vs_l = p.vs_l; a.os_h = p.os_h; a.os_l = p.os_l;
+#define DHSA_LAUNCH(CLS, tile0, T)                                                                           \
+    if ((T) > 0) {                                                                                          \
         const int mode = attn_order(want, p.H_kv, p.G, T);                                                  \
-        hipLaunchKernelGGL((k_attn_mfma<DD, PAR>), dim3(p.H_q * (T)), dim3(256), 0, s, pv, tile0, T,        \
-                           (const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O,    \
-                           p.H_q, p.G, mode, c, p.qs_h, p.qs_l, p.ks_h, p.ks_l, p.vs_h, p.vs_l,      \
-                           p.os_h, p.os_l);                                                                 \
+        if (p.D == 64)                                                                                      \
+            hipLaunchKernelGGL((k_attn_mfma<64, CLS>), dim3(p.H_q * (T)), dim3(256), 0, s, pv, a, p.H_q, mode, tile0, T);  \
+        else                                                                                                \
+            hipLaunchKernelGGL((k_attn_mfma<128, CLS>), dim3(p.H_q * (T)), dim3(256), 0, s, pv, a, p.H_q, mode, tile0, T); \
     }
-    // tiles of more than 64 rows first (they take longest), then the key-parity tiles
-    const int T_big = pv.T_big, T_small = pv.T1 - pv.T_big;
-    if (T_big > 0) { if (p.D == 64) DHSA_MFMA(64, false, 0, T_big) else DHSA_MFMA(128, false, 0, T_big) }
-    if (T_small > 0) { if (p.D == 64) DHSA_MFMA(64, true, T_big, T_small) else DHSA_MFMA(128, true, T_big, T_small) }
-#undef DHSA_MFMA
+    // tallest tiles first (they take longest)
+    DHSA_LAUNCH(0, 0, pv.T_big)
+    DHSA_LAUNCH(1, pv.T_big, pv.T_cls[2])
+    DHSA_LAUNCH(2, pv.T_big + pv.T_cls[2], pv.T_cls[3])
+#undef DHSA_LAUNCH
     return hipGetLastError();
 }
+
+#undef DHSA_SEGMENT_TABLE
+#undef DHSA_MAKE_META
+#undef DHSA_OFFS
+#undef DHSA_GLOAD
+#undef DHSA_LOAD_K_LO
+#undef DHSA_LOAD_K_HI
+#undef DHSA_LOAD_V
+#undef DHSA_LOAD_V_LO
+#undef DHSA_LOAD_V_HI
 
 }  // namespace dhsa

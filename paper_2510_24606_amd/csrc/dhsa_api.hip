@@ -103,18 +103,20 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     std::vector<int32_t> lens(p.N_c);
     for (int k = 0; k < p.N_c; ++k) lens[k] = B[k + 1] - B[k];
     pl.guess = first_list_guess(p, lens);
-    int64_t T1 = 0, T_big = 0;
+    // row tiles: every query group is cut into pieces of 128 rows and a remainder
+    int64_t cls[4] = {0, 0, 0, 0};
+    auto add_group = [&cls](int64_t len, int64_t times) {
+        cls[0] += times * (len / kRowTile);
+        if (len % kRowTile) cls[tile_class((int)(len % kRowTile))] += times;
+    };
     if (p.B_r > 0) {
-        const int64_t full = p.L / p.B_r, tail = p.L % p.B_r;     // row blocks of B_r rows, one shorter block
-        T1 = full * ((p.B_r + kRowTile - 1) / kRowTile) + (tail + kRowTile - 1) / kRowTile;
-        T_big = full * (p.B_r / kRowTile + (p.B_r % kRowTile > kRowTile / 2)) +
-                tail / kRowTile + (tail % kRowTile > kRowTile / 2);
+        add_group(p.B_r, p.L / p.B_r);            // row blocks of B_r rows, one shorter block
+        if (p.L % p.B_r) add_group(p.L % p.B_r, 1);
     } else {
-        for (int k = 0; k < p.N_c; ++k) {
-            T1 += (lens[k] + kRowTile - 1) / kRowTile;
-            T_big += lens[k] / kRowTile + (lens[k] % kRowTile > kRowTile / 2);
-        }
+        for (int k = 0; k < p.N_c; ++k) add_group(lens[k], 1);
     }
+    const int64_t T1 = cls[0] + cls[1] + cls[2] + cls[3], T_big = cls[0] + cls[1];
+    for (int c = 0; c < 4; ++c) pl.T_cls[c] = (int)cls[c];
     pl.stride = listed_bound(p, lens);
     pl.T1 = (int)T1;
     pl.T_big = (int)T_big;
@@ -148,6 +150,7 @@ DecodeLayout decode_layout(int H_q, int H_kv, int D, int64_t N_b, int N_c_cap, i
     PlanLayout &pl = dl.pl;
     pl.stride = pl.guess = 0;   // set per step
     pl.T1 = pl.T_big = 0;
+    pl.T_cls[0] = pl.T_cls[1] = pl.T_cls[2] = pl.T_cls[3] = 0;
     pl.N_q = 1;
     pl.off_B = 0;
     pl.off_RB = align_up((int64_t)N_c_cap + 1, 4);
@@ -177,6 +180,7 @@ PlanView plan_view(const PlanLayout &pl, const void *plan) {
     v.stride = pl.stride;
     v.T1 = pl.T1;
     v.T_big = pl.T_big;
+    for (int c = 0; c < 4; ++c) v.T_cls[c] = pl.T_cls[c];
     v.N_q = pl.N_q;
     return v;
 }
@@ -354,6 +358,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
         return DHSA_ERR_PLAN;
     PlanLayout pl;
     pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12]; pl.N_q = hdr[14]; pl.guess = 0;
+    pl.T_cls[0] = pl.T_cls[1] = pl.T_cls[2] = pl.T_cls[3] = 0;   // the expansion does not use the tile table
     pl.off_B = hdr[8]; pl.off_RB = hdr[13]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
     pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
     if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;

@@ -29,6 +29,7 @@ struct PlanLayout {
     int stride;       // entries per (h, l)
     int T1;           // row tiles per head
     int T_big;        // ... of which have more than 64 rows (listed first)
+    int T_cls[4];     // tiles of > 96, 65..96, 33..64 and <= 32 rows: the order of the tile table
     int N_q;          // query groups (chunks, or row blocks)
     int guess;        // chunks the ranking kernel lists first (see first_list_guess in dhsa_api.hip)
     int64_t off_B, off_RB, off_count, off_entries, off_tiles, words;
@@ -40,8 +41,9 @@ struct PlanView {
     const int32_t *RB;       // [N_q + 1] query group boundaries (== B when the groups are the chunks)
     const int32_t *count;    // [H_q][N_q]
     const int32_t *entries;  // [H_q][N_q][stride][2]
-    const int32_t *tiles;    // [T1][2]: first the T_big tiles of more than 64 rows, then the rest
+    const int32_t *tiles;    // [T1][2]: tiles of > 96 rows, then 65..96, 33..64, <= 32 rows (T_cls of each)
     int stride, T1, T_big, N_q;
+    int T_cls[4];
 };
 
 // Workspace layout in doubles.
@@ -137,6 +139,12 @@ __device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N
         if ((int64_t)B[mid] <= i) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+// Class of a row tile by its number of rows (1..128): the attention kernels give each class its
+// own arrangement of waves.  0: more than 96 rows, 1: 65..96, 2: 33..64, 3: at most 32.
+__host__ __device__ __forceinline__ int tile_class(int rows) {
+    return rows > 96 ? 0 : rows > 64 ? 1 : rows > 32 ? 2 : 3;
 }
 
 // Tokens row (visible own-chunk count v) takes from a plan entry.  For pos = 3

@@ -16,13 +16,13 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 // Plan header, query-group boundaries and row-tile table.  One block; B is
 // already in the plan.  The query groups are the chunks themselves, or (Alg. 1
 // as printed) row blocks of B_r rows, RB[i] = min(i B_r, L).  Tiles are the
-// <= 128-row pieces of the query groups; the table lists first those of more
-// than 64 rows, then the others, each group ordered by row.
+// <= 128-row pieces of the query groups; the table lists them by class -- more
+// than 96 rows, 65..96, 33..64, at most 32 -- each class ordered by row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int N_c,
                                                int N_b, int64_t L, int B_r) {
-    __shared__ int s_big[256], s_small[256];
-    __shared__ int s_carry_big, s_carry_small;
+    __shared__ int s_n[4][256];    // tiles of each class per query group of the slab (scanned in place)
+    __shared__ int s_carry[4];
     const int tid = threadIdx.x;
     const int N_q = pl.N_q;
     int32_t *tiles = plan + pl.off_tiles;
@@ -58,42 +58,55 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
         }
         plan[tid] = w;
     }
-    if (tid == 0) { s_carry_big = 0; s_carry_small = pl.T_big; }
+    if (tid == 0) {   // where each class starts in the table
+        s_carry[0] = 0;
+        s_carry[1] = pl.T_cls[0];
+        s_carry[2] = pl.T_cls[0] + pl.T_cls[1];
+        s_carry[3] = pl.T_cls[0] + pl.T_cls[1] + pl.T_cls[2];
+    }
     __syncthreads();
     for (int base = 0; base < N_q; base += 256) {
         const int l = base + tid;
-        int b0 = 0, len = 0, nfull = 0, rem = 0;
+        int b0 = 0, nfull = 0, rem = 0;
         if (l < N_q) {
             b0 = B[l];
-            len = B[l + 1] - b0;
+            const int len = B[l + 1] - b0;
             nfull = len / kRowTile;
             rem = len % kRowTile;
         }
-        const int nbig = nfull + (rem > kRowTile / 2), nsmall = (rem > 0 && rem <= kRowTile / 2);
-        s_big[tid] = nbig;
-        s_small[tid] = nsmall;
+        const int rem_cls = rem > 0 ? tile_class(rem) : -1;
+        int mine[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            mine[c] = (c == 0 ? nfull : 0) + (rem_cls == c);
+            s_n[c][tid] = mine[c];
+        }
         __syncthreads();
         // Hillis-Steele inclusive scans over the 256 slab entries
         for (int off = 1; off < 256; off <<= 1) {
-            const int vb = (tid >= off) ? s_big[tid - off] : 0;
-            const int vs = (tid >= off) ? s_small[tid - off] : 0;
+            int v[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = (tid >= off) ? s_n[c][tid - off] : 0;
             __syncthreads();
-            s_big[tid] += vb;
-            s_small[tid] += vs;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s_n[c][tid] += v[c];
             __syncthreads();
         }
-        int at = s_carry_big + s_big[tid] - nbig;
-        for (int t = 0; t < nbig; ++t) {
+        int at = s_carry[0] + s_n[0][tid] - mine[0];
+        for (int t = 0; t < nfull; ++t) {
             tiles[2 * (at + t)] = l;
             tiles[2 * (at + t) + 1] = b0 + t * kRowTile;
         }
-        if (nsmall) {
-            at = s_carry_small + s_small[tid] - 1;
+        if (rem_cls >= 0) {
+            at = s_carry[rem_cls] + s_n[rem_cls][tid] - 1;
             tiles[2 * at] = l;
             tiles[2 * at + 1] = b0 + nfull * kRowTile;
         }
         __syncthreads();
-        if (tid == 255) { s_carry_big += s_big[255]; s_carry_small += s_small[255]; }
+        if (tid == 255) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s_carry[c] += s_n[c][255];
+        }
         __syncthreads();
     }
 }
@@ -467,10 +480,11 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
                 unsigned long long *ckey = reinterpret_cast<unsigned long long *>(smem + (size_t)P * 8);  // over id[]
                 int *cid = reinterpret_cast<int *>(ckey + kMaxCand);
                 const int per = (n + 255) / 256;
+                const bool all = shift == 64;   // no radix pass ran (n <= cap): every element is a candidate
                 int local = 0;
                 for (int e = 0; e < per; ++e) {
                     const int x = tid * per + e;
-                    if (x < n && (key[x] >> shift) >= prefix) ++local;
+                    if (x < n && (all || (key[x] >> shift) >= prefix)) ++local;
                 }
                 int total;
                 int slot = block_excl_scan(local, s_wave, &total);
@@ -478,7 +492,7 @@ __global__ __launch_bounds__(256) void k_select(const double *__restrict__ Sc, i
                 id_intact = false;
                 for (int e = 0; e < per; ++e) {
                     const int x = tid * per + e;
-                    if (x < n && (key[x] >> shift) >= prefix) { ckey[slot] = key[x]; cid[slot] = x; ++slot; }
+                    if (x < n && (all || (key[x] >> shift) >= prefix)) { ckey[slot] = key[x]; cid[slot] = x; ++slot; }
                 }
                 ns = total;
                 Ps = 64;

@@ -63,8 +63,9 @@ def check_plan_all_blocks(w, g, B_r):
     t = plan["tiles"]
     order = np.argsort(t[:, 1], kind="stable")
     nrows_t = np.r_[t[order][1:, 1], w.L] - t[order][:, 1]
-    big = np.zeros(len(t), dtype=bool); big[order] = nrows_t > 64
-    assert big[:plan["T_big"]].all() and not big[plan["T_big"]:].any()
+    nr = np.empty(len(t), dtype=np.int64); nr[order] = nrows_t
+    cls = np.where(nr > 96, 0, np.where(nr > 64, 1, np.where(nr > 32, 2, 3)))
+    assert (np.diff(cls) >= 0).all() and (cls < 2).sum() == plan["T_big"]
     t = t[order]
     assert t[0, 1] == 0
     ends = np.r_[t[1:, 1], w.L]

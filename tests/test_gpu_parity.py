@@ -60,13 +60,16 @@ def check_plan_all_chunks(w, g):
             np.testing.assert_array_equal(e[:, 0] & ((1 << dhsa.POS_SHIFT) - 1), ks)
             np.testing.assert_array_equal(e[:, 0] >> dhsa.POS_SHIFT, pos[l, ks])
             np.testing.assert_array_equal(e[:, 1], rem[l, ks])
-    # tile table: rows of one chunk, <= 128 each, covering [0, L); tiles of more than 64 rows first
+    # tile table: rows of one chunk, <= 128 each, covering [0, L); listed by class (more than 96 rows,
+    # 65..96, 33..64, at most 32), each class by row; the first T_big have more than 64 rows
     t = plan["tiles"]
     order = np.argsort(t[:, 1], kind="stable")
-    nrows_t = np.r_[t[order][1:, 1], w.L] - t[order][:, 1]
-    big = np.zeros(len(t), dtype=bool); big[order] = nrows_t > 64
-    assert big[:plan["T_big"]].all() and not big[plan["T_big"]:].any()
-    assert (np.diff(t[:plan["T_big"], 1]) > 0).all() and (np.diff(t[plan["T_big"]:, 1]) > 0).all()
+    nrows_t = np.empty(len(t), dtype=np.int64)
+    nrows_t[order] = np.r_[t[order][1:, 1], w.L] - t[order][:, 1]
+    cls = np.where(nrows_t > 96, 0, np.where(nrows_t > 64, 1, np.where(nrows_t > 32, 2, 3)))
+    assert (np.diff(cls) >= 0).all() and (cls < 2).sum() == plan["T_big"]
+    for c in range(4):
+        assert (np.diff(t[cls == c, 1]) > 0).all()
     t = t[order]
     assert t[0, 1] == 0
     ends = np.r_[t[1:, 1], w.L]
