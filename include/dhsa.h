@@ -39,7 +39,8 @@
  *     packed).  Row starts must be 16-byte aligned.
  *   - B is a HOST array of N_c+1 int32 with B[0] = 0 < B[1] < ... < B[N_c] = L;
  *     chunk k holds tokens [B[k], B[k+1]).  It is validated on the host before
- *     any device work and copied into the plan.
+ *     any device work and travels into the plan as kernel arguments (no copy from
+ *     host memory, which could make the call wait).
  *   - The caller owns every buffer (plan and workspace included, sized by the
  *     *_bytes calls, 256-byte aligned).  The library allocates nothing, keeps
  *     no state between calls, and never synchronises: work is enqueued on
@@ -115,9 +116,12 @@ typedef struct {
  * is the sparsity mask M of Sec. 3.1 in compact form: all rows of query chunk l
  * share one ranking and differ only in v = i + 1 - B[l], the visible part of
  * their own chunk.
- *   words [0, 16)            header: magic 'DHSA', version, H_q, N_c, N_b (clamped to L),
+ *   words [0, 32)            header: magic 'DHSA', version, H_q, N_c, N_b (clamped to L),
  *                            stride, L, T1 (row tiles per head), off_B, off_count,
- *                            off_entries, off_tiles (word offsets), T_big, off_RB, N_q, B_r
+ *                            off_entries, off_tiles (word offsets), T_big, off_RB, N_q, B_r,
+ *                            pooling, checksum of B (32-bit FNV-1a over its N_c + 1 words),
+ *                            H_kv, D, tiles of more than 96 / 65..96 / 33..64 / at most 32
+ *                            rows (4 words), 8 words zero
  *   off_B      int32[N_c+1]  the boundaries of the key chunks
  *   off_RB     int32[N_q+1]  the boundaries of the query groups: the same array as
  *                            off_B (N_q = N_c) when B_r = 0; else RB[i] = min(i B_r, L),
@@ -141,7 +145,8 @@ typedef struct {
  *                            (the first T_big have more than 64), each class by row
  */
 #define DHSA_PLAN_MAGIC 0x41534844
-#define DHSA_PLAN_VERSION 2
+#define DHSA_PLAN_VERSION 3
+#define DHSA_PLAN_HEADER_WORDS 32
 #define DHSA_ROW_TILE 128
 
 /* Device bytes the plan / the routing workspace need.  0 on invalid arguments. */
@@ -158,10 +163,21 @@ dhsa_status dhsa_route(const dhsa_problem *prob, const void *Q_dev, const void *
 /* Step 5 (Alg. 2 / Alg. 3): exact softmax attention over the keys the plan
  * selects, O_dev[h, i, :] for every row.  The plan must come from dhsa_route on
  * the same problem and boundaries (it may be reused across calls, as the paper
- * caches routing results). */
+ * caches routing results).  On the host only the plan's size can be checked
+ * (DHSA_ERR_PLAN if too small) since the call never waits for the device; the
+ * kernels compare the plan's header -- H_q, N_c, N_b, L, B_r, pooling, a checksum
+ * of B -- with the problem and, if they differ, leave without reading further or
+ * writing O.  dhsa_plan_check reports such a mismatch to the host. */
 dhsa_status dhsa_sparse_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
                                 const void *V_dev, const int32_t *B_host, const void *plan_dev,
                                 size_t plan_bytes, void *O_dev, void *stream);
+
+/* Does plan_dev belong to this problem and these boundaries?  Reads the plan's
+ * header back (so it WAITS for `stream`) and compares it with what dhsa_route
+ * would write: DHSA_OK, or DHSA_ERR_PLAN.  For callers that keep plans across
+ * calls (Sec. 3.4 caches routing results) and want the check on the host. */
+dhsa_status dhsa_plan_check(const dhsa_problem *prob, const int32_t *B_host, const void *plan_dev,
+                            size_t plan_bytes, void *stream);
 
 /* Steps 1-5 on one stream (Sec. 3.4 "Workflow"). */
 dhsa_status dhsa_prefill(const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev,
@@ -230,6 +246,23 @@ dhsa_status dhsa_plan_expand_rows(const dhsa_problem *prob, const void *plan_dev
  * filled.  N_q = N_c, or ceil(L / B_r) when B_r > 0.  NULL skips. */
 dhsa_status dhsa_debug_routing(const dhsa_problem *prob, const int32_t *B_host, const void *ws_dev,
                                size_t ws_bytes, double *Qc_dev, double *Kc_dev, double *Sc_dev, void *stream);
+
+/* S_c alone (Sec. 3.3), fp64 [H_q][N_q][N_c], out of a workspace dhsa_route has
+ * filled: dhsa_debug_routing with only the scores asked for. */
+dhsa_status dhsa_debug_scores(const dhsa_problem *prob, const int32_t *B_host, const void *ws_dev,
+                              size_t ws_bytes, double *Sc_dev, void *stream);
+
+/* Measurement aid (not a step of the method): dhsa_prefill run once with events
+ * between its kernels.  ms_host[0..7] (HOST floats) receive the milliseconds of:
+ * 0 boundaries + plan set-up, 1 chunk pooling (Eq. 4), 2 S_c, 3 ranking + budget
+ * (Alg. 1), 4 / 5 / 6 attention (Alg. 3) over the row tiles of more than 64 rows /
+ * of 33..64 rows / of at most 32 rows (fp32 inputs: all rows in slot 4), 7 the
+ * whole call.  Creates and destroys events and BLOCKS until the work is done;
+ * arguments and results otherwise as dhsa_prefill. */
+dhsa_status dhsa_prefill_stage_times(const dhsa_problem *prob, const void *Q_dev, const void *K_dev,
+                                     const void *V_dev, const int32_t *B_host, void *O_dev, void *plan_dev,
+                                     size_t plan_bytes, void *ws_dev, size_t ws_bytes, float *ms_host,
+                                     void *stream);
 
 /* Measurement aid (not a step of the method): the sustained rate of the bf16
  * matrix instruction the attention kernel (Alg. 3's QK^T and PV products) is

@@ -22,7 +22,8 @@ PLAN_MAGIC = 0x41534844
 POS_SHIFT = 28
 
 EXPORTS = ["dhsa_plan_bytes", "dhsa_workspace_bytes", "dhsa_route", "dhsa_sparse_prefill", "dhsa_prefill",
-           "dhsa_prefill_static", "dhsa_static_scratch_bytes",
+           "dhsa_prefill_static", "dhsa_static_scratch_bytes", "dhsa_plan_check", "dhsa_prefill_stage_times",
+           "dhsa_debug_scores",
            "dhsa_plan_expand_rows", "dhsa_debug_routing", "dhsa_mfma_probe", "dhsa_mfma_probe_scratch_bytes",
            "dhsa_finalize_boundaries", "dhsa_finalize_boundaries_workspace_bytes",
            "dhsa_recall_rows", "dhsa_recall_workspace_bytes",
@@ -69,6 +70,11 @@ def lib() -> C.CDLL:
         l.dhsa_prefill_static.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp]
         l.dhsa_prefill_static.restype = C.c_int
         l.dhsa_static_scratch_bytes.argtypes = []; l.dhsa_static_scratch_bytes.restype = C.c_size_t
+        l.dhsa_plan_check.argtypes = [P, i32p, vp, C.c_size_t, vp]; l.dhsa_plan_check.restype = C.c_int
+        l.dhsa_prefill_stage_times.argtypes = [P, vp, vp, vp, i32p, vp, vp, C.c_size_t, vp, C.c_size_t,
+                                               C.POINTER(C.c_float), vp]
+        l.dhsa_prefill_stage_times.restype = C.c_int
+        l.dhsa_debug_scores.argtypes = [P, i32p, vp, C.c_size_t, vp, vp]; l.dhsa_debug_scores.restype = C.c_int
         l.dhsa_plan_expand_rows.argtypes = [P, vp, C.c_size_t, C.c_int32, i64p, C.c_int32, vp, vp, C.c_int32, vp, vp]
         l.dhsa_plan_expand_rows.restype = C.c_int
         l.dhsa_debug_routing.argtypes = [P, i32p, vp, C.c_size_t, vp, vp, vp, vp]
@@ -181,6 +187,34 @@ def dhsa_prefill_static(prob, Q, K, V, B, O, plan) -> None:
     p = _with_vo(prob, V, O)
     _check(lib().dhsa_prefill_static(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B), O.data_ptr(),
                                      plan.data_ptr(), plan.numel(), _stream()))
+
+
+def dhsa_plan_check(prob, B, plan) -> None:
+    """Raises DhsaError (code 8) unless `plan` was routed for this problem and these boundaries.  Waits for the stream."""
+    B = _b(B)
+    _check(lib().dhsa_plan_check(C.byref(prob), _bp(B), plan.data_ptr(), plan.numel(), _stream()))
+
+
+STAGES = ("setup", "pool", "scores", "select", "attn_rows_gt64", "attn_rows_33_64", "attn_rows_le32", "total")
+
+
+def dhsa_prefill_stage_times(prob, Q, K, V, B, O, plan, ws) -> dict:
+    """One pass of the whole path with events between its kernels: {stage: ms}.  Blocks."""
+    B = _b(B)
+    p = _with_vo(prob, V, O)
+    ms = (C.c_float * 8)()
+    _check(lib().dhsa_prefill_stage_times(C.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _bp(B), O.data_ptr(),
+                                          plan.data_ptr(), plan.numel(), ws.data_ptr(), ws.numel(), ms, _stream()))
+    return dict(zip(STAGES, (float(x) for x in ms)))
+
+
+def dhsa_debug_scores(prob, B, ws):
+    """S_c [H_q, N_q, N_c] fp64 (entries of chunks a query group cannot see are zero here)."""
+    import torch
+    B = _b(B)
+    Sc = torch.zeros((prob.H_q, n_query_groups(prob), prob.N_c), dtype=torch.float64, device=ws.device)
+    _check(lib().dhsa_debug_scores(C.byref(prob), _bp(B), ws.data_ptr(), ws.numel(), Sc.data_ptr(), _stream()))
+    return Sc
 
 
 def dhsa_static_scratch_bytes() -> int:
@@ -308,6 +342,7 @@ def parse_plan(plan_host: np.ndarray) -> dict:
     oB, oC, oE, oT = (int(x) for x in w[8:12])
     oRB, N_q, B_r = int(w[13]), int(w[14]), int(w[15])
     return dict(H_q=H_q, N_c=N_c, N_b=N_b, stride=stride, L=L, T1=T1, T_big=int(w[12]), N_q=N_q, B_r=B_r,
+                pooling=int(w[16]), b_sum=int(w[17]), H_kv=int(w[18]), D=int(w[19]), T_cls=[int(x) for x in w[20:24]],
                 B=w[oB:oB + N_c + 1], RB=w[oRB:oRB + N_q + 1],
                 count=w[oC:oC + H_q * N_q].reshape(H_q, N_q),
                 entries=w[oE:oE + H_q * N_q * stride * 2].reshape(H_q, N_q, stride, 2),

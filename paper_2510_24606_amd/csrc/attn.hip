@@ -50,6 +50,7 @@ __global__ __launch_bounds__(256) void k_attn_rowwise(PlanView pv, const T *__re
     constexpr int EP = RowIO<T>::kPer16;
     constexpr int NC = D / 64;  // output columns per lane
     __shared__ float s_q[4][D];
+    if (!plan_matches(pv)) return;   // not this problem's plan: O is not written
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.y, g = h / G;
     const int64_t i = (int64_t)blockIdx.x * 4 + wave;

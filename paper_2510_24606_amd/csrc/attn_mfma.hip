@@ -882,6 +882,7 @@ __device__ __forceinline__ void attn_tile_16(AttnSmem<D> &sm, const PlanView &pv
 template <int D, int CLS>
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, AttnArgs a, int H_q, int mode, int tile0, int T) {
     __shared__ AttnSmem<D> sm;
+    if (!plan_matches(pv)) return;   // not this problem's plan: nothing is read further, O is not written
     int h, pos;
     decode_block(mode, blockIdx.x, H_q, a.G, T, &h, &pos);
     const int tile = tile0 + T - 1 - pos;
@@ -891,7 +892,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, AttnArgs a, i
 }
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
-                            void *O, hipStream_t s) {
+                            void *O, hipStream_t s, hipEvent_t *ev) {
     const int want = 8;   // kv-heads in flight: one per XCD (other orders measured within 2 %)
     AttnArgs a;
     a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V; a.O = (uint16_t *)O;
@@ -909,8 +910,11 @@ hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, co
     }
     // tallest tiles first (they take longest)
     DHSA_LAUNCH(0, 0, pv.T_big)
+    if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;
     DHSA_LAUNCH(1, pv.T_big, pv.T_cls[2])
+    if (ev && hipEventRecord(ev[1], s) != hipSuccess) return hipErrorUnknown;
     DHSA_LAUNCH(2, pv.T_big + pv.T_cls[2], pv.T_cls[3])
+    if (ev && hipEventRecord(ev[2], s) != hipSuccess) return hipErrorUnknown;
 #undef DHSA_LAUNCH
     return hipGetLastError();
 }

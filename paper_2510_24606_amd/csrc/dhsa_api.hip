@@ -103,6 +103,9 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     std::vector<int32_t> lens(p.N_c);
     for (int k = 0; k < p.N_c; ++k) lens[k] = B[k + 1] - B[k];
     pl.guess = first_list_guess(p, lens);
+    uint32_t fnv = 2166136261u;                   // FNV-1a over the words of B
+    for (int k = 0; k <= p.N_c; ++k) fnv = (fnv ^ (uint32_t)B[k]) * 16777619u;
+    pl.b_sum = (int32_t)fnv;
     // row tiles: every query group is cut into pieces of 128 rows and a remainder
     int64_t cls[4] = {0, 0, 0, 0};
     auto add_group = [&cls](int64_t len, int64_t times) {
@@ -121,7 +124,7 @@ PlanLayout plan_layout(const Prob &p, const int32_t *B) {
     pl.T1 = (int)T1;
     pl.T_big = (int)T_big;
     pl.N_q = p.N_q;
-    pl.off_B = 16;
+    pl.off_B = kPlanHeaderWords;
     pl.off_RB = p.B_r > 0 ? align_up(pl.off_B + p.N_c + 1, 4) : pl.off_B;
     pl.off_count = align_up(pl.off_RB + p.N_q + 1, 4);
     pl.off_entries = align_up(pl.off_count + (int64_t)p.H_q * p.N_q, 4);
@@ -148,7 +151,7 @@ DecodeLayout decode_layout(int H_q, int H_kv, int D, int64_t N_b, int N_c_cap, i
     dl.off_Sc = align_up(dl.off_Qc + (int64_t)H_q * D * 8, 256);
     dl.off_plan = align_up(dl.off_Sc + (int64_t)H_q * N_c_cap * 8, 256);
     PlanLayout &pl = dl.pl;
-    pl.stride = pl.guess = 0;   // set per step
+    pl.stride = pl.guess = pl.b_sum = 0;   // set per step
     pl.T1 = pl.T_big = 0;
     pl.T_cls[0] = pl.T_cls[1] = pl.T_cls[2] = pl.T_cls[3] = 0;
     pl.N_q = 1;
@@ -169,9 +172,12 @@ bool decode_caps_ok(const dhsa_problem *prob, int32_t N_c_cap, int64_t L_cap) {
            prob->N_b >= 1 && N_c_cap >= 1 && N_c_cap <= kMaxChunks && L_cap >= 1 && L_cap < (int64_t)1 << 31;
 }
 
-PlanView plan_view(const PlanLayout &pl, const void *plan) {
+PlanView plan_view(const Prob &p, const PlanLayout &pl, const void *plan) {
     const int32_t *w = static_cast<const int32_t *>(plan);
     PlanView v;
+    v.hdr = w;
+    v.sig.H_q = p.H_q; v.sig.N_c = p.N_c; v.sig.N_b = p.N_b; v.sig.L = (int32_t)p.L; v.sig.B_r = p.B_r;
+    v.sig.N_q = pl.N_q; v.sig.pooling = p.pooling; v.sig.b_sum = pl.b_sum; v.sig.stride = pl.stride; v.sig.T1 = pl.T1;
     v.B = w + pl.off_B;
     v.RB = w + pl.off_RB;
     v.count = w + pl.off_count;
@@ -187,31 +193,34 @@ PlanView plan_view(const PlanLayout &pl, const void *plan) {
 
 dhsa_status hip_status(hipError_t e) { return e == hipSuccess ? DHSA_OK : DHSA_ERR_HIP; }
 
-// b_by_args: the boundaries travel as kernel arguments instead of a copy from host memory
+// ev (may be null): events recorded after set-up, pooling, scores and ranking
 dhsa_status route_impl(const Prob &p, const PlanLayout &pl, const WsLayout &wl, const void *Q, const void *K,
-                       const int32_t *B_host, void *plan, void *ws, hipStream_t s, bool b_by_args = false) {
+                       const int32_t *B_host, void *plan, void *ws, hipStream_t s, hipEvent_t *ev = nullptr) {
     int32_t *pw = static_cast<int32_t *>(plan);
     double *wd = static_cast<double *>(ws);
-    hipError_t e = b_by_args ? launch_put_boundaries(B_host, p.N_c + 1, pw + pl.off_B, s)
-                             : hipMemcpyAsync(pw + pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
-                                              hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return DHSA_ERR_HIP;
-    if ((e = launch_setup(p, pl, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
-    if ((e = launch_pool(p, Q, K, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Qc, wd + wl.off_Kc, s)) != hipSuccess)
+    // the boundaries travel as kernel arguments: no copy from (pageable) host memory, nothing that can wait
+    if (launch_put_boundaries(B_host, p.N_c + 1, pw + pl.off_B, s) != hipSuccess) return DHSA_ERR_HIP;
+    if (launch_setup(p, pl, pw, s) != hipSuccess) return DHSA_ERR_HIP;
+    if (ev && hipEventRecord(ev[0], s) != hipSuccess) return DHSA_ERR_HIP;
+    if (launch_pool(p, Q, K, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Qc, wd + wl.off_Kc, s) != hipSuccess)
         return DHSA_ERR_HIP;
-    if ((e = launch_scores(p, wd + wl.off_Qc, wd + wl.off_Kc, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Sc, s)) !=
+    if (ev && hipEventRecord(ev[1], s) != hipSuccess) return DHSA_ERR_HIP;
+    if (launch_scores(p, wd + wl.off_Qc, wd + wl.off_Kc, pw + pl.off_B, pw + pl.off_RB, wd + wl.off_Sc, s) !=
         hipSuccess)
         return DHSA_ERR_HIP;
-    if ((e = launch_select(p, pl, wd + wl.off_Sc, pw, s)) != hipSuccess) return DHSA_ERR_HIP;
+    if (ev && hipEventRecord(ev[2], s) != hipSuccess) return DHSA_ERR_HIP;
+    if (launch_select(p, pl, wd + wl.off_Sc, pw, s) != hipSuccess) return DHSA_ERR_HIP;
+    if (ev && hipEventRecord(ev[3], s) != hipSuccess) return DHSA_ERR_HIP;
     return DHSA_OK;
 }
 
+// ev (may be null): three events, see launch_attn_mfma
 dhsa_status attend_impl(const Prob &p, const PlanLayout &pl, const void *Q, const void *K, const void *V,
-                        const void *plan, void *O, hipStream_t s) {
-    const PlanView pv = plan_view(pl, plan);
-
-    hipError_t e = (p.dtype == DHSA_BF16) ? launch_attn_mfma(p, pv, Q, K, V, O, s)
-                                          : launch_attn_rowwise(p, pv, Q, K, V, O, s);
+                        const void *plan, void *O, hipStream_t s, hipEvent_t *ev = nullptr) {
+    const PlanView pv = plan_view(p, pl, plan);
+    if (p.dtype == DHSA_BF16) return hip_status(launch_attn_mfma(p, pv, Q, K, V, O, s, ev));
+    hipError_t e = launch_attn_rowwise(p, pv, Q, K, V, O, s);
+    for (int i = 0; ev && i < 3 && e == hipSuccess; ++i) e = hipEventRecord(ev[i], s);
     return hip_status(e);
 }
 
@@ -329,9 +338,63 @@ __attribute__((visibility("default"))) dhsa_status dhsa_prefill_static(const dhs
     hipStream_t s = static_cast<hipStream_t>(stream);
     // nothing in the scratch has to start at zero: the pooled vectors and every score the ranking
     // reads are written by this call before they are read
-    st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws, s, /*b_by_args=*/true);
+    st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws, s);
     if (st != DHSA_OK) return st;
     return attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s);
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_plan_check(const dhsa_problem *prob, const int32_t *B_host,
+                                                                   const void *plan_dev, size_t plan_bytes,
+                                                                   void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!plan_dev) return DHSA_ERR_NULL;
+    if (misaligned(plan_dev)) return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    if (plan_bytes < (size_t)pl.words * 4) return DHSA_ERR_PLAN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t hdr[kPlanHeaderWords];
+    if (hipMemcpyAsync(hdr, plan_dev, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return DHSA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return DHSA_ERR_HIP;
+    const int32_t want[18] = {DHSA_PLAN_MAGIC, DHSA_PLAN_VERSION, p.H_q, p.N_c, p.N_b, pl.stride, (int32_t)p.L, pl.T1,
+                              (int32_t)pl.off_B, (int32_t)pl.off_count, (int32_t)pl.off_entries,
+                              (int32_t)pl.off_tiles, pl.T_big, (int32_t)pl.off_RB, pl.N_q, p.B_r, p.pooling, pl.b_sum};
+    for (int i = 0; i < 18; ++i)
+        if (hdr[i] != want[i]) return DHSA_ERR_PLAN;
+    return DHSA_OK;
+}
+
+__attribute__((visibility("default"))) dhsa_status dhsa_prefill_stage_times(
+    const dhsa_problem *prob, const void *Q_dev, const void *K_dev, const void *V_dev, const int32_t *B_host,
+    void *O_dev, void *plan_dev, size_t plan_bytes, void *ws_dev, size_t ws_bytes, float *ms_host, void *stream) {
+    Prob p;
+    dhsa_status st = resolve(prob, B_host, &p);
+    if (st != DHSA_OK) return st;
+    if (!Q_dev || !K_dev || !V_dev || !plan_dev || !O_dev || !ws_dev || !ms_host) return DHSA_ERR_NULL;
+    if (misaligned(Q_dev) || misaligned(K_dev) || misaligned(V_dev) || misaligned(plan_dev) ||
+        misaligned(O_dev) || misaligned(ws_dev))
+        return DHSA_ERR_ALIGN;
+    const PlanLayout pl = plan_layout(p, B_host);
+    const WsLayout wl = ws_layout(p);
+    if (plan_bytes < (size_t)pl.words * 4 || ws_bytes < (size_t)wl.doubles * 8) return DHSA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t ev[8];   // start, then the end of each of the seven stages
+    int made = 0;
+    for (; made < 8; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) break;
+    st = made == 8 ? DHSA_OK : DHSA_ERR_HIP;
+    if (st == DHSA_OK && hipEventRecord(ev[0], s) != hipSuccess) st = DHSA_ERR_HIP;
+    if (st == DHSA_OK) st = route_impl(p, pl, wl, Q_dev, K_dev, B_host, plan_dev, ws_dev, s, ev + 1);
+    if (st == DHSA_OK) st = attend_impl(p, pl, Q_dev, K_dev, V_dev, plan_dev, O_dev, s, ev + 5);
+    if (st == DHSA_OK && hipEventSynchronize(ev[7]) != hipSuccess) st = DHSA_ERR_HIP;
+    if (st == DHSA_OK) {
+        for (int i = 0; i < 7 && st == DHSA_OK; ++i)
+            if (hipEventElapsedTime(&ms_host[i], ev[i], ev[i + 1]) != hipSuccess) st = DHSA_ERR_HIP;
+        if (st == DHSA_OK && hipEventElapsedTime(&ms_host[7], ev[0], ev[7]) != hipSuccess) st = DHSA_ERR_HIP;
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return st;
 }
 
 __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
@@ -346,10 +409,10 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
     if (cap < nb) return DHSA_ERR_WORKSPACE;
     for (int t = 0; t < n_rows; ++t)
         if (rows_host[t] < 0 || rows_host[t] >= prob->L) return DHSA_ERR_SHAPE;
-    if (plan_bytes < 64) return DHSA_ERR_PLAN;
+    if (plan_bytes < sizeof(int32_t) * kPlanHeaderWords) return DHSA_ERR_PLAN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // read the header back: the layout offsets are part of the plan
-    int32_t hdr[16];
+    int32_t hdr[kPlanHeaderWords];
     if (hipMemcpyAsync(hdr, plan_dev, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return DHSA_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return DHSA_ERR_HIP;
     if (hdr[0] != DHSA_PLAN_MAGIC || hdr[1] != DHSA_PLAN_VERSION || hdr[2] != prob->H_q || hdr[3] != prob->N_c ||
@@ -358,6 +421,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
         return DHSA_ERR_PLAN;
     PlanLayout pl;
     pl.stride = hdr[5]; pl.T1 = hdr[7]; pl.T_big = hdr[12]; pl.N_q = hdr[14]; pl.guess = 0;
+    pl.b_sum = hdr[17];                                          // no boundaries here to check it against
     pl.T_cls[0] = pl.T_cls[1] = pl.T_cls[2] = pl.T_cls[3] = 0;   // the expansion does not use the tile table
     pl.off_B = hdr[8]; pl.off_RB = hdr[13]; pl.off_count = hdr[9]; pl.off_entries = hdr[10]; pl.off_tiles = hdr[11];
     pl.words = pl.off_tiles + 2 * (int64_t)pl.T1;
@@ -365,11 +429,12 @@ __attribute__((visibility("default"))) dhsa_status dhsa_plan_expand_rows(
     Prob p;
     memset(&p, 0, sizeof(p));
     p.L = prob->L; p.H_q = prob->H_q; p.N_c = prob->N_c; p.N_b = nb; p.B_r = prob->B_r; p.N_q = pl.N_q;
+    p.pooling = hdr[16];
     if (n_rows == 0) return DHSA_OK;
     if (hipMemcpyAsync(rows_dev_scratch, rows_host, sizeof(int64_t) * (size_t)n_rows, hipMemcpyHostToDevice, s) !=
         hipSuccess)
         return DHSA_ERR_HIP;
-    return hip_status(launch_expand(p, plan_view(pl, plan_dev), head, rows_dev_scratch, n_rows, idx_dev, cap,
+    return hip_status(launch_expand(p, plan_view(p, pl, plan_dev), head, rows_dev_scratch, n_rows, idx_dev, cap,
                                     cnt_dev, s));
 }
 
@@ -403,14 +468,13 @@ __attribute__((visibility("default"))) dhsa_status dhsa_decode_step(
     int32_t *plan = reinterpret_cast<int32_t *>(static_cast<char *>(ws_dev) + dl.off_plan);
     // The boundaries B[0 .. kc_valid] are in the workspace already (the caller vouches for it).  The
     // others travel as kernel arguments when they are few (the usual step adds one or two), so that a
-    // steady-state step issues no copy from host memory; otherwise all of B is copied.
+    // steady-state step needs no launch for them; otherwise all of B is sent (as arguments of small kernels).
     BoundaryTail tail;
     tail.n = 0;
     if (kc_valid > 0 && p.N_c - kc_valid <= kBoundaryTailMax) {
         tail.n = p.N_c - kc_valid;
         for (int j = 0; j <= tail.n; ++j) tail.b[j] = B_host[kc_valid + j];
-    } else if (hipMemcpyAsync(plan + dl.pl.off_B, B_host, sizeof(int32_t) * (size_t)(p.N_c + 1),
-                              hipMemcpyHostToDevice, s) != hipSuccess) {
+    } else if (launch_put_boundaries(B_host, p.N_c + 1, plan + dl.pl.off_B, s) != hipSuccess) {
         return DHSA_ERR_HIP;
     }
     if (launch_decode_route(p, dl, N_c_cap, kc_valid, rb0, tail, Q_dev, K_dev, ws_dev, s) != hipSuccess)
@@ -445,7 +509,7 @@ __attribute__((visibility("default"))) dhsa_status dhsa_recall_rows(
     if (hipMemcpyAsync(rows_dev_scratch, rows_host, sizeof(int64_t) * (size_t)n_rows, hipMemcpyHostToDevice, s) !=
         hipSuccess)
         return DHSA_ERR_HIP;
-    return hip_status(launch_recall(p, plan_view(pl, plan_dev), Q_dev, K_dev, head, rows_dev_scratch, n_rows,
+    return hip_status(launch_recall(p, plan_view(p, pl, plan_dev), Q_dev, K_dev, head, rows_dev_scratch, n_rows,
                                     static_cast<unsigned long long *>(ws_dev), hits_dev, size_dev, s));
 }
 
@@ -475,6 +539,13 @@ __attribute__((visibility("default"))) dhsa_status dhsa_debug_routing(const dhsa
     return hip_status(e);
 }
 
+__attribute__((visibility("default"))) dhsa_status dhsa_debug_scores(const dhsa_problem *prob, const int32_t *B_host,
+                                                                     const void *ws_dev, size_t ws_bytes,
+                                                                     double *Sc_dev, void *stream) {
+    if (!Sc_dev) return DHSA_ERR_NULL;
+    return dhsa_debug_routing(prob, B_host, ws_dev, ws_bytes, nullptr, nullptr, Sc_dev, stream);
+}
+
 __attribute__((visibility("default"))) const char *dhsa_status_string(dhsa_status s) {
     switch (s) {
         case DHSA_OK: return "ok";
@@ -491,6 +562,6 @@ __attribute__((visibility("default"))) const char *dhsa_status_string(dhsa_statu
     return "unknown status";
 }
 
-__attribute__((visibility("default"))) int dhsa_version(void) { return 120; }
+__attribute__((visibility("default"))) int dhsa_version(void) { return 200; }
 
 }  // extern "C"

@@ -24,6 +24,8 @@ struct Prob {
     int64_t qs_h, qs_l, ks_h, ks_l, vs_h, vs_l, os_h, os_l;
 };
 
+constexpr int kPlanHeaderWords = DHSA_PLAN_HEADER_WORDS;
+
 // Word offsets inside the plan buffer (see the layout comment in dhsa.h).
 struct PlanLayout {
     int stride;       // entries per (h, l)
@@ -32,11 +34,22 @@ struct PlanLayout {
     int T_cls[4];     // tiles of > 96, 65..96, 33..64 and <= 32 rows: the order of the tile table
     int N_q;          // query groups (chunks, or row blocks)
     int guess;        // chunks the ranking kernel lists first (see first_list_guess in dhsa_api.hip)
+    int b_sum;        // checksum of the boundaries (header word 17)
     int64_t off_B, off_RB, off_count, off_entries, off_tiles, words;
+};
+
+// What the caller's problem says a plan must have been built for.  Every kernel that reads a plan
+// compares this with the plan's header first and leaves without writing anything if they differ
+// (a plan routed for another budget, row-block size, representation or boundary array of equal
+// size would otherwise be used silently).
+struct PlanSig {
+    int32_t H_q, N_c, N_b, L, B_r, N_q, pooling, b_sum, stride, T1;
 };
 
 // Device-side view of a plan.
 struct PlanView {
+    const int32_t *hdr;      // [kPlanHeaderWords]
+    PlanSig sig;
     const int32_t *B;        // [N_c + 1] key chunk boundaries
     const int32_t *RB;       // [N_q + 1] query group boundaries (== B when the groups are the chunks)
     const int32_t *count;    // [H_q][N_q]
@@ -102,8 +115,10 @@ hipError_t launch_recall(const Prob &p, const PlanView &pv, const void *Q, const
                          hipStream_t s);
 hipError_t launch_attn_rowwise(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                                void *O, hipStream_t s);
+// ev (may be null): three events recorded after the launches of the tiles of more than 64 rows, of
+// 33..64 rows and of at most 32 rows
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
-                            void *O, hipStream_t s);
+                            void *O, hipStream_t s, hipEvent_t *ev = nullptr);
 
 // ---- small device helpers ----
 // bf16 storage type (a bare 16-bit pattern; the kernels convert by hand)
@@ -139,6 +154,13 @@ __device__ __forceinline__ int chunk_of_row(const int32_t *__restrict__ B, int N
         if ((int64_t)B[mid] <= i) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+__device__ __forceinline__ bool plan_matches(const PlanView &pv) {
+    const int32_t *w = pv.hdr;
+    return w[0] == DHSA_PLAN_MAGIC && w[1] == DHSA_PLAN_VERSION && w[2] == pv.sig.H_q && w[3] == pv.sig.N_c &&
+           w[4] == pv.sig.N_b && w[5] == pv.sig.stride && w[6] == pv.sig.L && w[7] == pv.sig.T1 &&
+           w[14] == pv.sig.N_q && w[15] == pv.sig.B_r && w[16] == pv.sig.pooling && w[17] == pv.sig.b_sum;
 }
 
 // Class of a row tile by its number of rows (1..128): the attention kernels give each class its

@@ -32,6 +32,7 @@ __global__ __launch_bounds__(256) void k_recall(PlanView pv, const T *__restrict
     __shared__ int s_hist[256];
     __shared__ int s_wave[4];
     __shared__ int s_digit, s_above, s_equal;
+    if (!plan_matches(pv)) return;   // not this problem's plan: nothing is written
     const int t = blockIdx.x, tid = threadIdx.x;
     const int64_t i = rows[t];
     const int n = (int)(i + 1);

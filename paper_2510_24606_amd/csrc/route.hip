@@ -19,8 +19,8 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 // <= 128-row pieces of the query groups; the table lists them by class -- more
 // than 96 rows, 65..96, 33..64, at most 32 -- each class ordered by row.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int N_c,
-                                               int N_b, int64_t L, int B_r) {
+__global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanLayout pl, int H_q, int H_kv, int D,
+                                               int N_c, int N_b, int64_t L, int B_r, int pooling) {
     __shared__ int s_n[4][256];    // tiles of each class per query group of the slab (scanned in place)
     __shared__ int s_carry[4];
     const int tid = threadIdx.x;
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
         __syncthreads();
     }
     const int32_t *B = plan + pl.off_RB;   // the boundaries the rows are grouped by
-    if (tid < 16) {
+    if (tid < kPlanHeaderWords) {
         int32_t w = 0;
         switch (tid) {
             case 0: w = DHSA_PLAN_MAGIC; break;
@@ -54,6 +54,11 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
             case 13: w = (int32_t)pl.off_RB; break;
             case 14: w = N_q; break;
             case 15: w = B_r; break;
+            case 16: w = pooling; break;
+            case 17: w = pl.b_sum; break;
+            case 18: w = H_kv; break;
+            case 19: w = D; break;
+            case 20: case 21: case 22: case 23: w = pl.T_cls[tid - 20]; break;
             default: break;
         }
         plan[tid] = w;
@@ -112,7 +117,8 @@ __global__ __launch_bounds__(256) void k_setup(int32_t *__restrict__ plan, PlanL
 }
 
 hipError_t launch_setup(const Prob &p, const PlanLayout &pl, int32_t *plan, hipStream_t s) {
-    hipLaunchKernelGGL(k_setup, dim3(1), dim3(256), 0, s, plan, pl, p.H_q, p.N_c, p.N_b, p.L, p.B_r);
+    hipLaunchKernelGGL(k_setup, dim3(1), dim3(256), 0, s, plan, pl, p.H_q, p.H_kv, p.D, p.N_c, p.N_b, p.L, p.B_r,
+                       p.pooling);
     return hipGetLastError();
 }
 
@@ -635,6 +641,7 @@ hipError_t launch_select_groups(const Prob &p, const PlanLayout &pl, const doubl
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_expand(PlanView pv, int N_c, int head, const int64_t *__restrict__ rows,
                                                int32_t *__restrict__ idx, int cap, int32_t *__restrict__ cnt) {
+    if (!plan_matches(pv)) return;   // not this problem's plan: nothing is written
     const int t = blockIdx.x, lane = threadIdx.x;
     const int64_t i = rows[t];
     const int l = chunk_of_row(pv.RB, pv.N_q, i);

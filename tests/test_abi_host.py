@@ -64,7 +64,7 @@ def test_sizes(lib):
 
 
 def test_plan_size_follows_the_documented_layout(lib):
-    """Plan words = header 16 | B | counts | entries [H_q][N_c][stride][2] | tiles, where stride =
+    """Plan words = header 32 | B | counts | entries [H_q][N_c][stride][2] | tiles, where stride =
     min(N_c, n + 2) and n = how many of the shortest chunks have lengths summing to less than N_b
     (recomputed here with a sort; the library counts lengths, and sorts only for very long chunks)."""
     rng = np.random.default_rng(3)
@@ -86,7 +86,7 @@ def test_plan_size_follows_the_documented_layout(lib):
             acc += int(srt[n]); n += 1
         stride = min(N_c, n + 2)
         T1 = int(((lens + 127) // 128).sum())
-        off_count = al(16 + N_c + 1, 4)
+        off_count = al(32 + N_c + 1, 4)
         off_entries = al(off_count + H_q * N_c, 4)
         off_tiles = al(off_entries + H_q * N_c * stride * 2, 4)
         words = al(off_tiles + 2 * T1, 64)
