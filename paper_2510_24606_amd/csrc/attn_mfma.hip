@@ -83,12 +83,13 @@ struct AttnSmem {
     alignas(16) unsigned key_voff[8][kKT];
     alignas(16) int key_lo[8][kKT];
     alignas(16) int key_hi[8][kKT];
-    alignas(16) int seg_start[kSegB + 16];
+    alignas(16) int seg_start[kSegB + 80];   // the entries past the last segment hold the batch's key count
+    int meta_tmp[4][kKT];                   // per wave: marks of the segment starts inside a tile
     int seg_b0[kSegB];
     int seg_pos[kSegB];
     int seg_rem[kSegB];
     int flags[8];
-    int s_wave[4];
+    int s_wave[8];
 };
 
 // blockIdx -> (head, tile).  Workgroups are dealt to the 8 XCDs round-robin and
@@ -126,48 +127,64 @@ static int attn_order(int want, int H_kv, int G, int T1) {
 // b_l, row0, nrows, k_row_bytes, v_row_bytes, off_slot_wr, off_slot_rd, lds_K,
 // lds_V, Kg8, Vg8, ld_piece_bytes_k / _v, ko_lo, ko_hi, vo, KPT, kTile).
 // ---------------------------------------------------------------------------
-// Segment table of the batch of plan entries [e0, e0 + kSegB) for this tile: per entry the first
-// packed position of its keys (sm.seg_start, an exclusive scan of the most tokens any row of the
-// tile takes from the entry; for the row-block form keys past the tile's last row are dropped),
-// the chunk's first token, pos and rem.  Defines `total`, the packed keys of the batch.  Contains
-// block barriers.
+// Segment table of the batch of plan entries [e0, e0 + kSegB) for this tile.  A segment is an entry
+// some row of the tile takes a key from; segments are stored compacted, in entry order: the first
+// packed position of their keys (an exclusive scan of the most tokens any row of the tile takes
+// from the entry; for the row-block form keys past the tile's last row are dropped), the chunk's
+// first token, pos and rem.  Defines `total` (packed keys of the batch), `nseg` and the wave's
+// segment cursor.  Contains block barriers.
 #define DHSA_SEGMENT_TABLE(e0) \
-    int n_e = 0; \
+    int n_e = 0, b0_e = 0, pos_e = 0, rem_e = 0; \
     if (e0 + tid < E) { \
-        const int w0 = ent[2 * (e0 + tid)], rem = ent[2 * (e0 + tid) + 1]; \
-        const int k = w0 & kChunkMask, pos = w0 >> kPosShift; \
-        const int b0 = pv.B[k]; \
-        n_e = entry_take(pos, rem, pv.B[k + 1] - b0, pos == 1 ? v_hi : v_lo); \
-        if (pos == 3) { \
-            const int vis = row0 + nrows - b0; \
+        const int w0 = ent[2 * (e0 + tid)]; \
+        rem_e = ent[2 * (e0 + tid) + 1]; \
+        const int k = w0 & kChunkMask; \
+        pos_e = w0 >> kPosShift; \
+        b0_e = pv.B[k]; \
+        n_e = entry_take(pos_e, rem_e, pv.B[k + 1] - b0_e, pos_e == 1 ? v_hi : v_lo); \
+        if (pos_e == 3) { \
+            const int vis = row0 + nrows - b0_e; \
             n_e = vis < n_e ? (vis > 0 ? vis : 0) : n_e; \
         } \
-        sm.seg_b0[tid] = b0; \
-        sm.seg_pos[tid] = pos; \
-        sm.seg_rem[tid] = rem; \
     } \
-    int total; \
-    const int start = block_excl_scan(n_e, sm.s_wave, &total); \
-    sm.seg_start[tid] = start; \
-    if (tid < 16) sm.seg_start[kSegB + tid] = total; \
+    int total, nseg, start, slot; \
+    block_excl_scan2(n_e, n_e > 0 ? 1 : 0, sm.s_wave, &start, &slot, &total, &nseg); \
+    if (n_e > 0) { \
+        sm.seg_start[slot] = start; \
+        sm.seg_b0[slot] = b0_e; \
+        sm.seg_pos[slot] = pos_e; \
+        sm.seg_rem[slot] = rem_e; \
+    } \
+    for (int i_ = nseg + tid; i_ < kSegB + 80; i_ += 256) sm.seg_start[i_] = total; \
+    int seg_cur = 0; \
     __syncthreads();
 
-// one wave: packed position -> (row offsets, lo, hi) of tile n.  The segment of a
-// position is found with two 16-way steps over the sorted segment starts.
+// one wave: packed position -> (row offsets, lo, hi) of tile n.  The tiles a wave prepares come in
+// ascending order, so the segment of the tile's first key is found by moving the wave's cursor
+// forward (64 segment starts per look); the starts that fall inside the tile then mark their
+// position, and a key's segment is the first one plus the marks at or before the key.
 #define DHSA_MAKE_META(n)                                                                       \
     {                                                                                           \
         const int buf_ = (n) & 7;                                                               \
-        int x_ = (n) * kKT + lane;                                                              \
-        const bool pad_ = x_ >= total;                                                          \
-        if (pad_) x_ = total - 1;                                                               \
-        int c_ = -1;                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) c_ += (sm.seg_start[16 * i_] <= x_);  \
-        int f_ = -1;                                                                            \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                      \
-            const int4 q_ = *reinterpret_cast<const int4 *>(&sm.seg_start[16 * c_ + 4 * i_]);   \
-            f_ += (q_.x <= x_) + (q_.y <= x_) + (q_.z <= x_) + (q_.w <= x_);                    \
+        const int x0_ = (n) * kKT;                                                              \
+        int s0_ = seg_cur;                                                                      \
+        for (;;) {                                                                              \
+            const int a_ = __popcll(__ballot(sm.seg_start[s0_ + 1 + lane] <= x0_));             \
+            s0_ += a_;                                                                          \
+            if (a_ < 64) break;                                                                 \
         }                                                                                       \
-        const int seg_ = 16 * c_ + f_;                                                          \
+        seg_cur = s0_;                                                                          \
+        const int p_ = sm.seg_start[s0_ + 1 + lane] - x0_;                                      \
+        /* lanes talk through LDS without a block barrier: volatile keeps the three accesses  */ \
+        /* in program order (the LDS executes one wave's operations in order)                 */ \
+        volatile int *const mt_ = sm.meta_tmp[wave_u];                                          \
+        mt_[lane] = 0;                                                                          \
+        if (p_ > 0 && p_ < kKT) mt_[p_] = 1;                                                    \
+        const unsigned long long marks_ = __ballot(mt_[lane] != 0);                             \
+        int x_ = x0_ + lane;                                                                    \
+        int seg_ = s0_ + __popcll(marks_ & ((2ull << lane) - 1ull));                            \
+        const bool pad_ = x_ >= total;                                                          \
+        if (pad_) { x_ = total - 1; seg_ = nseg - 1; }                                          \
         const int t_ = x_ - sm.seg_start[seg_];                                                 \
         const int pos_ = sm.seg_pos[seg_];                                                      \
         const unsigned j_ = (unsigned)(sm.seg_b0[seg_] + t_);                                   \

@@ -204,4 +204,29 @@ __device__ __forceinline__ int block_excl_scan(int val, int *s_wave, int *total)
     return base + inc - val;
 }
 
+// Two exclusive prefix sums at once (same barriers as one).
+__device__ __forceinline__ void block_excl_scan2(int a, int b, int *s_wave8, int *excl_a, int *excl_b, int *total_a,
+                                                 int *total_b) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int ia = a, ib = b;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int ta = __shfl_up(ia, off), tb = __shfl_up(ib, off);
+        if (lane >= off) { ia += ta; ib += tb; }
+    }
+    __syncthreads();  // protects s_wave8 from its previous use
+    if (lane == 63) { s_wave8[wave] = ia; s_wave8[4 + wave] = ib; }
+    __syncthreads();
+    int base_a = 0, base_b = 0, tot_a = 0, tot_b = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int xa = s_wave8[w], xb = s_wave8[4 + w];
+        if (w < wave) { base_a += xa; base_b += xb; }
+        tot_a += xa; tot_b += xb;
+    }
+    *total_a = tot_a; *total_b = tot_b;
+    *excl_a = base_a + ia - a;
+    *excl_b = base_b + ib - b;
+}
+
 }  // namespace dhsa
