@@ -212,8 +212,16 @@ def test_peaky_softmax_moves_the_exponent_reference():
         # near one-hot rows return single value vectors, |O| up to ~4.5 here: rounding O to bf16
         # costs up to |O| * 2^-8 (half an ulp), rounding the probabilities another |O| * 2^-9
         tol = np.abs(O_ref).max() * (2.0 ** -8 + 2.0 ** -9) * 1.05
-        print(f"   {name}: peaky softmax max |O - oracle| = {err:.3e} (bound {tol:.3e})", flush=True)
+        # The 2e-2 bar of the other tests is an absolute one for outputs of unit scale; here the bound
+        # above is ~2.8e-2 because |O| is ~4.5.  Relative to the row's own magnitude the error meets
+        # the same bar: asserted too, and both figures are printed.
+        rel = (np.abs(got - O_ref).max(axis=2) / np.maximum(np.abs(O_ref).max(axis=2), 1.0)).max()
+        over = int((np.abs(got - O_ref).max(axis=2) > TOL["bf16"]).sum())
+        print(f"   {name}: peaky softmax max |O - oracle| = {err:.3e} (bound {tol:.3e}); {over} of "
+              f"{got.shape[0] * got.shape[1]} rows above 2e-2 absolute; max error relative to max(|O_row|, 1) = "
+              f"{rel:.3e}", flush=True)
         assert err <= tol
+        assert rel <= TOL["bf16"]
 
 
 FULL = ["c2", "c3", "c4", "c5"]
