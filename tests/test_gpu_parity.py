@@ -128,6 +128,31 @@ def test_small_full_parity(name, kw):
           f"max |O - oracle| = {err:.3e}", flush=True)
 
 
+def test_row_tiles_at_the_edges_of_the_height_classes():
+    """Chunks whose last row tile has exactly 1, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128 rows
+    (alone and behind one or two full tiles): every wave arrangement of the attention kernels at the edge
+    of its range, all rows compared."""
+    rem = [1, 16, 17, 31, 32, 33, 48, 63, 64, 65, 80, 95, 96, 97, 112, 127, 128]
+    lens = [r + 128 * f for f in (0, 1, 2) for r in rem]
+    rng = np.random.default_rng(5)
+    rng.shuffle(lens)
+    B = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    L = int(B[-1])
+    for D, N_b in ((128, 700), (64, 90)):
+        w = dhsa_inputs.make("c2", L=L, H_q=4, H_kv=2, D=D, N_b=N_b, lens=("fixed", 1))
+        w.B = B                                       # iid rows: nothing in Q, K, V depends on the boundaries
+        w.Q, w.K, w.V = (t.clone() for t in (w.Q, w.K, w.V))
+        g = run_gpu(w)
+        rows = np.arange(L, dtype=np.int64)
+        O_ref, I_ref, cnt_ref = oracle.prefill_rows(w.f32("Q"), w.f32("K"), w.f32("V"), w.B, w.N_b, rows)
+        check_mask_rows(w, g, rows, I_ref, cnt_ref)
+        check_plan_all_chunks(w, g)
+        err = check_outputs(w, g, rows, O_ref)
+        plan = dhsa.parse_plan(g["plan"].cpu().numpy())
+        assert all(c > 0 for c in plan["T_cls"])      # all four height classes occur
+        print(f"   D={D}: {len(lens)} chunks, tiles per class {plan['T_cls']}, max |O - oracle| = {err:.3e}", flush=True)
+
+
 def plans_equal(a, b):
     """Compare the defined words of two plans (slots past `count` are unspecified)."""
     pa, pb = dhsa.parse_plan(a.cpu().numpy()), dhsa.parse_plan(b.cpu().numpy())
