@@ -8,6 +8,10 @@
 // position (softmax is order-free) and packed densely into tiles of 64 keys;
 // a packed key carries (row offset, lo, hi) with "row takes key <=> lo < v < hi".
 //
+// Row tiles are launched by height: tiles of more than 64 rows on the body
+// described next (attn_tile_32), tiles of at most 64 and at most 32 rows on 16-row
+// MFMA blocks (attn_tile_16, described at that function), one launch each.
+//
 // Four waves; each owns one 32-row block.  Scores are computed transposed,
 // S^T = K Q^T (keys are the MFMA M dimension), so a lane holds 16 keys of ONE
 // query row per 32-key block: the row max / sum stay in the lane (one exchange
