@@ -41,11 +41,15 @@ ROW_CLASSES = (("rows_gt64", "attn_rows_gt64"), ("rows_33_64", "attn_rows_33_64"
 
 
 def kernel_source_hash() -> str:
-    """Identifies the attention kernel the counters in profiles/ were taken with."""
+    """Identifies the attention kernel the counters in profiles/ were taken with: a hash of its source
+    without // comments and blank lines (a reworded comment does not make the counters stale)."""
     h = hashlib.sha256()
     for rel in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, rel), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, rel), "r") as f:
+            for line in f:
+                code = line.split("//", 1)[0].rstrip()
+                if code.strip():
+                    h.update(code.encode() + b"\n")
     return h.hexdigest()[:16]
 
 
