@@ -135,6 +135,35 @@ def test_bad_boundaries_and_buffers(lib):
         assert len(lib.dhsa_status_string(s)) > 1
 
 
+def test_static_scratch_plan_check_and_stage_times_reject_bad_arguments_on_the_host(lib):
+    p, B = mk(), bounds()
+    bp = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    assert dhsa.dhsa_static_scratch_bytes() == 64 << 20
+    # dhsa_prefill_static: NULL, misaligned, plan too small, and a problem beyond the static scratch
+    assert lib.dhsa_prefill_static(C.byref(p), 16, 16, None, bp(B), 16, 16, 1 << 30, None) == 1
+    assert lib.dhsa_prefill_static(C.byref(p), 16, 16, 16, bp(B), 24, 16, 1 << 30, None) == 9
+    assert lib.dhsa_prefill_static(C.byref(p), 16, 16, 16, bp(B), 16, 16, 8, None) == 6
+    big_B = np.arange(8193, dtype=np.int32)
+    big = mk(L=8192, H_q=64, H_kv=1, D=64, N_c=8192, N_b=16, dtype=dhsa.DHSA_F32)
+    assert dhsa.dhsa_workspace_bytes(big, big_B) > dhsa.dhsa_static_scratch_bytes()
+    assert lib.dhsa_prefill_static(C.byref(big), 16, 16, 16, bp(big_B), 16, 16, 1 << 40, None) == 6
+    bad = np.r_[0, 200, 100, bounds()[3:]].astype(np.int32)
+    assert lib.dhsa_prefill_static(C.byref(p), 16, 16, 16, bp(bad), 16, 16, 1 << 30, None) == 3
+    # dhsa_plan_check
+    assert lib.dhsa_plan_check(C.byref(p), bp(B), None, 1 << 30, None) == 1
+    assert lib.dhsa_plan_check(C.byref(p), bp(B), 24, 1 << 30, None) == 9
+    assert lib.dhsa_plan_check(C.byref(p), bp(B), 16, 8, None) == 8
+    assert lib.dhsa_plan_check(C.byref(mk(N_b=0)), bp(B), 16, 1 << 30, None) == 4
+    # dhsa_prefill_stage_times
+    ms = (C.c_float * 8)()
+    assert lib.dhsa_prefill_stage_times(C.byref(p), 16, 16, 16, bp(B), 16, 16, 1 << 30, 16, 1 << 30, None, None) == 1
+    assert lib.dhsa_prefill_stage_times(C.byref(p), 16, 16, 16, bp(B), 16, 16, 8, 16, 1 << 30, ms, None) == 6
+    assert lib.dhsa_prefill_stage_times(C.byref(mk(D=96)), 16, 16, 16, bp(B), 16, 16, 1 << 30, 16, 1 << 30, ms, None) == 2
+    # dhsa_debug_scores
+    assert lib.dhsa_debug_scores(C.byref(p), bp(B), 16, 1 << 30, None, None) == 1
+    assert lib.dhsa_debug_scores(C.byref(p), bp(B), 16, 8, 16, None) == 6
+
+
 def test_mfma_probe_rejects_bad_arguments_on_the_host(lib):
     import ctypes as C
     tf = C.c_double(0.0)
