@@ -914,12 +914,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(PlanView pv, AttnArgs a, i
 
 hipError_t launch_attn_mfma(const Prob &p, const PlanView &pv, const void *Q, const void *K, const void *V,
                             void *O, hipStream_t s, hipEvent_t *ev) {
-    // kv-heads in flight: one per XCD when the K and V of eight heads fit the 256 MB memory-side
-    // cache (or when not even four do); else four, each on two XCDs, so that what the L2s miss is
-    // mostly served from that cache (c3: 537 MB for eight heads; four in flight measured 4 % faster
-    // on row blocks, 1.3 % on the row form; two or one in flight slower again)
+    // kv-heads in flight: one per XCD (most workgroups walking the same K / V per L2).  Row blocks of
+    // full tile height whose K and V of eight heads exceed the 256 MB memory-side cache while those of
+    // four fit: four in flight, each on two XCDs -- the L2s then miss more often (53 % hits instead of
+    // 56 % on c3) but mostly into that cache, and the step measures 4-5 % faster; the row form on the
+    // dynamic chunks, which is bound by what crosses the fabric, gains nothing from it (0-1 %) and asks
+    // the fabric for 30 % more, so it keeps eight.  Two or one in flight are slower in both forms.
     const double kv_head_bytes = 2.0 * (double)p.L * (double)(p.ks_l + p.vs_l);
-    const int want = (8 * kv_head_bytes <= 288e6 || 4 * kv_head_bytes > 288e6) ? 8 : 4;
+    const int want = (p.B_r >= kRowTile && 8 * kv_head_bytes > 288e6 && 4 * kv_head_bytes <= 288e6) ? 4 : 8;
     AttnArgs a;
     a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V; a.O = (uint16_t *)O;
     a.G = p.G;
